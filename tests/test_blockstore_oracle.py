@@ -1,0 +1,184 @@
+"""Pins for the structural oracle (oracle/blockstore_oracle.c): the paper's block store
+(section 4.1) with the sizing rule b_v = min(deg(v), tau), and Algorithm 1 (section 4.2)
+walked over it.  Results must not depend on the layout, so they are compared with the
+layout-free oracle over thresholds, sizing methods and ingestion splits; the layout
+itself is checked against closed forms and the paper's stated properties."""
+import numpy as np
+import pytest
+
+from paper_2311_17410_amd import workloads as W
+
+
+def build(oracle, st, tau, sizing, batch):
+    bs = oracle.BlockStore(st.num_nodes, tau, sizing)
+    bs.add_stream(st.src, st.dst, st.ts, batch)
+    return bs
+
+
+# ---- sizing rule: closed forms ---------------------------------------------------------
+
+def test_adaptive_one_edge_per_batch_doubles_until_tau(oracle_lib):
+    # a node that receives one edge per ingestion batch: capacities 1,1,2,4,8,... capped at tau
+    tau, m = 16, 100
+    bs = oracle_lib.BlockStore(1, tau, oracle_lib.BlockStore.ADAPTIVE)
+    for i in range(m):
+        bs.add_batch([0], [i], [float(i)])
+    caps = list(bs.blocks()["cap"])
+    expect, stored = [], 0
+    while stored < m:
+        cap = max(1, min(stored, tau))
+        expect.append(cap)
+        stored += cap
+    assert caps == expect
+    assert caps[:6] == [1, 1, 2, 4, 8, 16] and set(caps[6:]) == {16}
+    b = bs.blocks()
+    assert np.all(b["size"][:-1] == b["cap"][:-1])          # only the tail may have room
+
+
+def test_batch_larger_than_formula_gets_one_block(oracle_lib):
+    bs = oracle_lib.BlockStore(2, 8, oracle_lib.BlockStore.ADAPTIVE)
+    bs.add_batch([0] * 5, [1] * 5, [0, 1, 2, 3, 4])             # new node, deg 0 -> block of 5
+    assert list(bs.blocks()["cap"]) == [5]
+    bs.add_batch([0] * 3, [1] * 3, [5, 6, 7])                   # deg 5 < tau -> min(5, 8) = 5
+    assert list(bs.blocks()["cap"]) == [5, 5] and list(bs.blocks()["size"]) == [5, 3]
+    bs.add_batch([0] * 30, [1] * 30, np.arange(8, 38))          # fills 2, then 28 > tau in one block
+    assert list(bs.blocks()["cap"]) == [5, 5, 28]
+    bs.add_batch([0], [1], [40])                                # deg 38 >= tau -> tau
+    assert list(bs.blocks()["cap"]) == [5, 5, 28, 8]
+    assert bs.stats()["wasted_slots"] == 7
+
+
+def test_strawman_and_fixed_sizes(oracle_lib):
+    src = [0] * 10
+    dst = list(range(10))
+    ts = list(range(10))
+    s = oracle_lib.BlockStore(1, 4, oracle_lib.BlockStore.STRAWMAN)
+    s.add_batch(src[:3], dst[:3], ts[:3]); s.add_batch(src[3:], dst[3:], ts[3:])
+    assert list(s.blocks()["cap"]) == [3, 7] and s.stats()["wasted_slots"] == 0
+    f = oracle_lib.BlockStore(1, 4, oracle_lib.BlockStore.FIXED)
+    f.add_batch(src[:3], dst[:3], ts[:3]); f.add_batch(src[3:], dst[3:], ts[3:])
+    assert list(f.blocks()["cap"]) == [4, 4, 4] and list(f.blocks()["size"]) == [4, 4, 2]
+
+
+# ---- P9 structural invariants + waste bound of section 4.1 ------------------------------
+
+@pytest.mark.parametrize("tau,batch", [(1, 64), (48, 128), (8192, 1 << 12), (48, 1 << 20)])
+def test_p9_structure(oracle_lib, tau, batch):
+    st = W.zipf_stream(np.random.Generator(np.random.PCG64(9)), 1 << 14, 1 << 9, batch, 1.1, "normal")
+    bs = build(oracle_lib, st, tau, 0, batch)
+    b = bs.blocks()
+    deg = np.bincount(st.src, minlength=st.num_nodes)
+    assert np.array_equal(np.bincount(b["node"], weights=b["size"], minlength=st.num_nodes).astype(np.int64), deg)
+    stats = bs.stats()
+    assert stats["edges"] == st.n
+    # the bound the paper states: wasted slots below half of ... the stored edges at worst
+    assert stats["wasted_slots"] < st.n
+    order = np.argsort(st.src, kind="stable")
+    starts = np.concatenate([[0], np.cumsum(deg)])
+    for v in range(min(st.num_nodes, 40)):
+        sel = np.nonzero(b["node"] == v)[0]
+        assert np.all(np.diff(sel) == 1) or len(sel) <= 1
+        seg = st.ts[order[starts[v]:starts[v + 1]]]
+        off = 0
+        for i in sel:
+            sz = int(b["size"][i])
+            assert sz >= 1 and b["t_min"][i] == seg[off] and b["t_max"][i] == seg[off + sz - 1]
+            if i != sel[-1]:
+                assert sz == b["cap"][i]
+            off += sz
+        nbr, eid, ts = bs.node_edges(v, int(deg[v]) + 1)
+        assert np.array_equal(eid, order[starts[v]:starts[v + 1]].astype(np.int32))
+        assert np.array_equal(nbr, st.dst[eid]) and np.array_equal(ts, st.ts[eid])
+
+
+# ---- P10 trends that hold for any stream ------------------------------------------------
+
+def test_p10_trends(oracle_lib):
+    wl = W.c3(log2_n=18)              # same recipe as C3, smaller: hub gets ~12% of the events
+    st = wl.streams[0]
+    batch = 1 << 11
+    nbatches = st.n // batch
+    static = build(oracle_lib, st, 8192, 0, st.n)
+    s = static.stats()
+    assert s["max_list_len"] == 1 and s["wasted_slots"] == 0
+    straw = build(oracle_lib, st, 8192, 1, batch)
+    adapt = build(oracle_lib, st, 256, 0, batch)
+    fixed = build(oracle_lib, st, 16, 2, batch)
+    bl_s = np.bincount(straw.blocks()["node"], minlength=st.num_nodes)
+    bl_a = np.bincount(adapt.blocks()["node"], minlength=st.num_nodes)
+    assert np.all(bl_s >= bl_a)
+    assert straw.stats()["wasted_slots"] == 0
+    hub = int(np.argmax(np.bincount(st.src)))
+    assert bl_a[hub] <= nbatches                      # about one block per batch on the hub
+    bl_f = np.bincount(fixed.blocks()["node"], minlength=st.num_nodes)
+    assert bl_f[hub] > 4 * bl_a[hub]                  # small fixed blocks: hub list much longer
+
+
+# ---- P7 layout independence ---------------------------------------------------------------
+
+@pytest.mark.parametrize("policy", [0, 1])
+@pytest.mark.parametrize("inclusive", [0, 1])
+def test_p7_results_do_not_depend_on_layout(oracle_lib, policy, inclusive):
+    st = W.tiny_stream(41, 3000, 23, 256, ties=True)
+    adj = oracle_lib.Adjacency(st.num_nodes, st.src, st.dst, st.ts)
+    targets, t_start, t_end = W.random_queries(42, st, 700)
+    q2 = (st.src, None, st.ts)
+    for f in (1, 3, 10):
+        ref = adj.sample(targets, t_start, t_end, fanout=f, policy=policy, inclusive_end=inclusive, seed=3)
+        ref2 = adj.sample(*q2, fanout=f, policy=policy, inclusive_end=inclusive, seed=3)
+        for tau in (1, 48, 8192, 2 ** 31 - 1):
+            for sizing in (0, 1, 2):
+                if sizing == 2 and tau > 8192:
+                    continue
+                for batch in (3000, 375, 7, 1):
+                    if batch == 1 and (tau != 48 or f != 3):
+                        continue
+                    bs = build(oracle_lib, st, tau, sizing, batch)
+                    got = bs.sample(targets, t_start, t_end, fanout=f, policy=policy, inclusive_end=inclusive, seed=3)
+                    for name in ("nbr", "eid", "ts", "count"):
+                        assert np.array_equal(getattr(got, name), getattr(ref, name)), (name, f, tau, sizing, batch)
+                    got2 = bs.sample(*q2, fanout=f, policy=policy, inclusive_end=inclusive, seed=3)
+                    assert np.array_equal(got2.eid, ref2.eid) and np.array_equal(got2.count, ref2.count)
+                    bs.close()
+
+
+def test_alg1_on_c1_matches_definition(oracle_lib):
+    wl = W.c1()
+    st = wl.streams[0]
+    adj = oracle_lib.Adjacency(st.num_nodes, st.src, st.dst, st.ts)
+    bs = build(oracle_lib, st, wl.tau, 0, st.batch)
+    targets, t_start, t_end, _ = wl.queries(window_frac=0.25)
+    for tb in (None, t_start):
+        for pol in (0, 1):
+            a = adj.sample(targets, tb, t_end, fanout=wl.fanout, policy=pol, seed=1)
+            b = bs.sample(targets, tb, t_end, fanout=wl.fanout, policy=pol, seed=1)
+            assert np.array_equal(a.eid, b.eid) and np.array_equal(a.nbr, b.nbr)
+            assert np.array_equal(a.ts, b.ts) and np.array_equal(a.count, b.count)
+
+
+def test_out_of_order_batch_rejected_and_store_unchanged(oracle_lib):
+    bs = oracle_lib.BlockStore(2, 4, 0)
+    bs.add_batch([0, 0], [1, 1], [1.0, 5.0])
+    with pytest.raises(oracle_lib.OracleError) as ei:
+        bs.add_batch([1, 0], [0, 0], [6.0, 4.0])
+    assert ei.value.code == -2
+    assert bs.stats()["edges"] == 2
+    bs.add_batch([0, 0], [1, 1], [7.0, 5.0])               # sorted inside the batch: 5 then 7
+    nbr, eid, ts = bs.node_edges(0, 10)
+    assert list(ts) == [1.0, 5.0, 5.0, 7.0] and list(eid) == [0, 1, 3, 2]
+
+
+def test_deletion_filters_before_selection(oracle_lib):
+    st = W.tiny_stream(51, 400, 3, 50)
+    bs = build(oracle_lib, st, 8, 0, 50)
+    rng = np.random.default_rng(1)
+    present = np.ones(st.n, np.uint8)
+    for e in rng.choice(st.n, 120, replace=False):
+        assert bs.delete_edge(int(st.src[e]), int(e)) == 1
+        present[e] = 0
+    adj = oracle_lib.Adjacency(st.num_nodes, st.src, st.dst, st.ts, present=present)
+    targets, t_start, t_end = W.random_queries(52, st, 200)
+    for pol in (0, 1):
+        a = adj.sample(targets, t_start, t_end, fanout=5, policy=pol, seed=2)
+        b = bs.sample(targets, t_start, t_end, fanout=5, policy=pol, seed=2)
+        assert np.array_equal(a.eid, b.eid) and np.array_equal(a.count, b.count)

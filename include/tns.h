@@ -1,0 +1,203 @@
+/*
+ * tns -- one-hop temporal neighbourhood sampling over a time-indexed, block-based dynamic
+ * graph store, on one AMD MI355X (gfx950).
+ *
+ * The operations follow GNNFlow (arXiv 2311.17410):
+ *   - the store is the node table + per-node chronological list of edge blocks of
+ *     section 4.1, with the block size rule b_v = min(deg(v), tau) ("Adaptive block sizing
+ *     with threshold");
+ *   - tns_run executes Algorithm 1 (section 4.2) for a batch of queries, with the recent
+ *     and uniform selection policies of section 2.1, writes the padded per-target result the
+ *     way section 4.2 "Kernel optimizations" asks for (consecutive slots per target) and
+ *     optionally removes the padding (section 5, "GPU-based sampling").
+ *
+ * Conventions
+ *   - Plain C ABI.  Every pointer argument is marked HOST or DEVICE.  DEVICE pointers are
+ *     ordinary HIP device allocations owned by the caller (e.g. torch tensors); HOST
+ *     pointers are ordinary host memory.  The library keeps no reference to any caller
+ *     buffer after a call returns (tns_run: after the work queued on the stream is done).
+ *   - ids are int32, timestamps are IEEE fp32, offsets are int64.
+ *   - All functions return 0 (TNS_OK) or a negative tns_status.  A failing call leaves the
+ *     plan unchanged.  tns_last_error() gives a human-readable detail for the last failure
+ *     on the calling thread.
+ *   - A plan is not thread-safe: one caller at a time.  tns_run only enqueues work on the
+ *     given stream and never blocks on the device, allocates or frees.
+ */
+#ifndef TNS_H
+#define TNS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#if defined(__GNUC__)
+#define TNS_API __attribute__((visibility("default")))
+#else
+#define TNS_API
+#endif
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tns_plan tns_plan; /* opaque: host-side store builder + device store */
+
+typedef enum {
+    TNS_OK = 0,
+    TNS_EINVAL = -1, /* null pointer, negative size, fanout out of range, bad enum value   */
+    TNS_EORDER = -2, /* NaN edge time, or a batch older than what a node already stores    */
+    TNS_ERANGE = -3, /* source node id or instance outside the configured range            */
+    TNS_ENOMEM = -4, /* host or device allocation failed                                   */
+    TNS_EHIP = -5,   /* HIP runtime error (no device, launch failure, ...)                 */
+    TNS_ESTATE = -6, /* tns_run before the first tns_commit                                */
+    TNS_ESIZE = -7   /* workspace too small, or a size beyond a documented limit           */
+} tns_status;
+
+enum { TNS_POLICY_RECENT = 0, TNS_POLICY_UNIFORM = 1 };
+enum { TNS_SIZING_ADAPTIVE = 0, TNS_SIZING_STRAWMAN = 1, TNS_SIZING_FIXED = 2 };
+enum { TNS_MAX_FANOUT = 64 };
+/* tns_config.flags */
+enum {
+    TNS_FLAG_NO_XCD_REMAP = 1 /* keep the hardware's round-robin workgroup->XCD order (for measurements) */
+};
+
+typedef struct {
+    int64_t num_nodes;       /* |V| per instance; node ids are 0 .. num_nodes-1                */
+    int32_t num_instances;   /* >= 1 independent graphs sharing this plan (ids are per instance) */
+    int32_t fanout;          /* f: neighbours sampled per target, 1 .. TNS_MAX_FANOUT (Alg. 1 input) */
+    int32_t policy;          /* TNS_POLICY_RECENT | TNS_POLICY_UNIFORM             (section 2.1) */
+    int32_t block_threshold; /* tau >= 1 of b_v = min(deg(v), tau)                 (section 4.1) */
+    int32_t sizing;          /* TNS_SIZING_*: adaptive is the paper's method; strawman and fixed
+                                are the comparison methods of section 6.2 (layout tests)        */
+    int32_t inclusive_end;   /* 0: window [t_s, t_e) as in Algorithm 1; 1: [t_s, t_e] as in
+                                section 2.1                                                    */
+    uint64_t seed;           /* uniform policy: key of the counter-based generator             */
+    int32_t device;          /* HIP device ordinal used by tns_commit / tns_run                */
+    int32_t flags;           /* TNS_FLAG_* bits, 0 for defaults                                */
+} tns_config;
+
+/*
+ * Create an empty store (section 4.1: node table with one entry per node, no blocks).
+ * Touches no GPU; the device is first used by tns_commit.  *out receives the plan.
+ */
+TNS_API int tns_plan_create(const tns_config *cfg, tns_plan **out);
+
+/*
+ * Ingest one batch of m edges into instance `instance` (section 4.1, edge insertion: append
+ * to the node's tail block while it has room, otherwise link a new block at the tail; the
+ * new block's capacity is max(remaining edges of this batch for the node,
+ * min(degree so far, tau))).  All arrays are HOST, length m, in arrival order; the edge
+ * src[i] -> dst[i] is stored with its source node (directed storage; store both directions
+ * yourself for an undirected graph).  eid may be NULL: ids then continue a per-instance
+ * running counter.  Inside the batch a node's edges are put in timestamp order (stable);
+ * TNS_EORDER if a node would receive an edge older than its newest stored edge or a NaN
+ * time, TNS_ERANGE for src outside [0, num_nodes).  Nothing is visible to tns_run until
+ * tns_commit.
+ */
+TNS_API int tns_add_edges(tns_plan *plan, int32_t instance, const int32_t *src, const int32_t *dst,
+                  const float *ts, const int32_t *eid, int64_t m);
+
+/*
+ * Make everything ingested so far visible to tns_run: uploads the changed parts of the
+ * node table, block records and edge data to the device (allocating or growing device
+ * memory as needed) on `hip_stream` (a hipStream_t, NULL = default stream) and waits for
+ * the upload.
+ */
+TNS_API int tns_commit(tns_plan *plan, void *hip_stream);
+
+/* Bytes of DEVICE workspace tns_run needs for Q queries when compaction is requested (0 otherwise). */
+TNS_API int tns_workspace(const tns_plan *plan, int64_t Q, size_t *bytes);
+
+/*
+ * Sample Q queries (Algorithm 1).  All d_* pointers are DEVICE.
+ *
+ *   d_targets[Q]      target node of each query (per-instance id); ids outside
+ *                     [0, num_nodes) and deleted nodes give count 0
+ *   d_t_start[Q]      window start, or NULL for -infinity
+ *   d_t_end[Q]        window end (open or closed per config.inclusive_end); NaN gives count 0
+ *   d_inst_rowptr     NULL when num_instances == 1; else [num_instances+1] non-decreasing query
+ *                     offsets, d_inst_rowptr[0] = 0, d_inst_rowptr[num_instances] = Q:
+ *                     queries d_inst_rowptr[b] .. d_inst_rowptr[b+1]-1 address instance b
+ *   query_id_base     id of query 0 for the uniform policy's generator (query i has id
+ *                     query_id_base + i); lets a long batch be run in pieces
+ *   d_out_nbr/eid/ts  [Q*fanout] padded result, row-major by query: slot j < count holds the
+ *                     neighbour id, edge id and timestamp of one sampled edge (recent: newest
+ *                     first; uniform: draw order); slots >= count hold -1, -1, 0.0f
+ *   d_out_count[Q]    number of filled slots per query, min(fanout, candidates)
+ *   d_rowptr[Q+1], d_cmp_nbr/eid/ts[sum of counts]
+ *                     padding removed: exclusive prefix sum of counts and the filled slots in
+ *                     (query, slot) order.  d_rowptr NULL (and the other three NULL) skips
+ *                     this step; the compacted arrays need room for Q*fanout entries in the
+ *                     worst case
+ *   d_workspace       at least tns_workspace() bytes, 256-byte aligned; may be NULL when
+ *                     compaction is skipped
+ *   hip_stream        hipStream_t on the plan's device (NULL = default stream)
+ *
+ * TNS_ESTATE before the first commit, TNS_ESIZE for a short workspace, TNS_EINVAL for
+ * missing pointers, TNS_EHIP if a launch fails.
+ */
+TNS_API int tns_run(tns_plan *plan, int64_t Q, const int32_t *d_targets, const float *d_t_start,
+            const float *d_t_end, const int64_t *d_inst_rowptr, int64_t query_id_base,
+            int32_t *d_out_nbr, int32_t *d_out_eid, float *d_out_ts, int32_t *d_out_count,
+            int64_t *d_rowptr, int32_t *d_cmp_nbr, int32_t *d_cmp_eid, float *d_cmp_ts,
+            void *d_workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Padding removal alone (section 5: after each sampling kernel the invalid neighbours are
+ * removed): the second half of tns_run, for callers that keep the two steps apart.  Reads the
+ * padded arrays and counts written by tns_run (DEVICE, same layout) and writes d_rowptr[Q+1]
+ * and the dense arrays as described there.  Same workspace and error rules as tns_run.
+ */
+TNS_API int tns_compact(tns_plan *plan, int64_t Q, const int32_t *d_out_nbr, const int32_t *d_out_eid,
+                        const float *d_out_ts, const int32_t *d_out_count, int64_t *d_rowptr,
+                        int32_t *d_cmp_nbr, int32_t *d_cmp_eid, float *d_cmp_ts, void *d_workspace,
+                        size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Byte model of a query batch: runs the walk of tns_run without producing results and adds
+ * to d_counters[0..3] (DEVICE, uint64, zeroed by the caller) the number of node entries, block
+ * records and edge timestamps the walk reads (Algorithm 1's node lookup, block steps and
+ * binary-search probes) and the number of edges it selects.  Query arguments as in tns_run.
+ */
+TNS_API int tns_traffic_model(tns_plan *plan, int64_t Q, const int32_t *d_targets, const float *d_t_start,
+                              const float *d_t_end, const int64_t *d_inst_rowptr, int64_t query_id_base,
+                              uint64_t *d_counters, void *hip_stream);
+
+/*
+ * Layout figures of one instance (the columns of the block-sizing table in section 6.2):
+ * average and maximum block-list length, bytes of edge data (all slots) and of metadata
+ * (node table + block records) as stored on the device, number of unfilled edge slots,
+ * number of blocks and of stored edges.  Any output pointer may be NULL.  instance = -1
+ * sums over all instances.
+ */
+typedef struct {
+    double avg_list_len;
+    int64_t max_list_len;
+    int64_t edge_data_bytes;
+    int64_t metadata_bytes;
+    int64_t wasted_slots;
+    int64_t num_blocks;
+    int64_t num_edges;
+} tns_stats_t;
+TNS_API int tns_stats(const tns_plan *plan, int32_t instance, tns_stats_t *out);
+
+/*
+ * Inspection of the host-side layout (for tests): the blocks of node `node` of `instance`
+ * from the oldest to the newest.  Arrays are HOST with room for `max_blocks` entries (any
+ * may be NULL); returns the node's block count (which may exceed max_blocks) or a negative
+ * status.
+ */
+TNS_API int64_t tns_node_blocks(const tns_plan *plan, int32_t instance, int32_t node, int64_t max_blocks,
+                        int32_t *cap, int32_t *size, float *t_min, float *t_max);
+
+/* Release the plan, its host store and its device memory.  NULL is allowed. */
+TNS_API int tns_destroy(tns_plan *plan);
+
+/* Static description of a status code. */
+TNS_API const char *tns_strerror(int status);
+/* Detail of the last failure on this thread ("" if none). Valid until the next tns call on the thread. */
+TNS_API const char *tns_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TNS_H */

@@ -1,0 +1,379 @@
+// C ABI of the library (include/tns.h): plan lifetime, ingestion, commit, run, statistics.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+#include <memory>
+#include <new>
+#include <string>
+
+#include "../../include/tns.h"
+#include "tns_kernels.h"
+#include "tns_store.h"
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const std::string& msg) {
+    g_err = msg;
+    return code;
+}
+
+int fail_hip(hipError_t e, const char* what) {
+    g_err = std::string(what) + ": " + hipGetErrorString(e);
+    (void)hipGetLastError();
+    return e == hipErrorOutOfMemory ? TNS_ENOMEM : TNS_EHIP;
+}
+
+// Switches to the plan's device for the lifetime of the object and restores the caller's.
+class DeviceGuard {
+public:
+    explicit DeviceGuard(int dev) {
+        ok_ = hipGetDevice(&prev_) == hipSuccess;
+        if (ok_ && prev_ != dev) {
+            err_ = hipSetDevice(dev);
+            switched_ = err_ == hipSuccess;
+        }
+        if (!ok_) err_ = hipErrorNoDevice;
+    }
+    ~DeviceGuard() {
+        if (switched_) (void)hipSetDevice(prev_);
+    }
+    hipError_t error() const { return err_; }
+
+private:
+    int prev_ = 0;
+    bool ok_ = false, switched_ = false;
+    hipError_t err_ = hipSuccess;
+};
+
+template <class T>
+struct DeviceArray {
+    T* ptr = nullptr;
+    int64_t cap = 0;   // elements allocated
+    int64_t used = 0;  // elements valid on the device
+};
+
+}  // namespace
+
+struct tns_plan {
+    tns_config cfg;
+    std::unique_ptr<tns::Store> store;
+    DeviceArray<tns::NodeRec> d_nodes;
+    DeviceArray<tns::BlockRec> d_blocks;
+    DeviceArray<tns::Edge> d_edges;
+    bool committed = false;
+};
+
+namespace {
+
+// Ensures room for `need` elements.  Growing reallocates; the host copy is complete, so the
+// whole array is simply marked for upload instead of being copied device to device.
+template <class T, class P>
+int ensure_capacity(DeviceArray<T>& d, int64_t need, P& host, const char* what) {
+    if (need <= d.cap) return TNS_OK;
+    int64_t cap = need + need / 4 + 1024;
+    T* p = nullptr;
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&p), (size_t)cap * sizeof(T));
+    if (e != hipSuccess) {
+        cap = need;
+        e = hipMalloc(reinterpret_cast<void**>(&p), (size_t)cap * sizeof(T));
+    }
+    if (e != hipSuccess) return fail_hip(e, what);
+    if (d.ptr) (void)hipFree(d.ptr);
+    d.ptr = p;
+    d.cap = cap;
+    d.used = 0;
+    host.mark_all();
+    return TNS_OK;
+}
+
+template <class T, class P>
+int upload_dirty(DeviceArray<T>& d, const P& host, hipStream_t stream, const char* what) {
+    hipError_t first = hipSuccess;
+    host.for_each_dirty([&](int64_t start, int64_t count, const T* src) {
+        if (first != hipSuccess) return;
+        first = hipMemcpyAsync(d.ptr + start, src, (size_t)count * sizeof(T), hipMemcpyHostToDevice, stream);
+    });
+    if (first != hipSuccess) return fail_hip(first, what);
+    d.used = host.size();
+    return TNS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tns_plan_create(const tns_config* cfg, tns_plan** out) {
+    g_err.clear();
+    if (!cfg || !out) return fail(TNS_EINVAL, "null config or output pointer");
+    if (cfg->num_nodes < 0 || cfg->num_nodes > (int64_t)INT32_MAX) return fail(TNS_EINVAL, "num_nodes must be in [0, 2^31-1]");
+    if (cfg->num_instances < 1) return fail(TNS_EINVAL, "num_instances must be >= 1");
+    if (cfg->fanout < 1 || cfg->fanout > TNS_MAX_FANOUT) return fail(TNS_EINVAL, "fanout must be in [1, 64]");
+    if (cfg->policy != TNS_POLICY_RECENT && cfg->policy != TNS_POLICY_UNIFORM) return fail(TNS_EINVAL, "unknown policy");
+    if (cfg->block_threshold < 1) return fail(TNS_EINVAL, "block_threshold (tau) must be >= 1");
+    if (cfg->sizing < 0 || cfg->sizing > 2) return fail(TNS_EINVAL, "unknown sizing method");
+    if (cfg->inclusive_end != 0 && cfg->inclusive_end != 1) return fail(TNS_EINVAL, "inclusive_end must be 0 or 1");
+    if (cfg->device < 0) return fail(TNS_EINVAL, "negative device ordinal");
+    try {
+        std::unique_ptr<tns_plan> p(new tns_plan());
+        p->cfg = *cfg;
+        tns::StoreConfig sc;
+        sc.num_nodes = cfg->num_nodes;
+        sc.num_instances = cfg->num_instances;
+        sc.tau = cfg->block_threshold;
+        sc.sizing = cfg->sizing;
+        p->store.reset(new tns::Store(sc));
+        *out = p.release();
+    } catch (const std::bad_alloc&) {
+        return fail(TNS_ENOMEM, "host allocation failed");
+    }
+    return TNS_OK;
+}
+
+int tns_add_edges(tns_plan* plan, int32_t instance, const int32_t* src, const int32_t* dst, const float* ts,
+                  const int32_t* eid, int64_t m) {
+    g_err.clear();
+    if (!plan) return fail(TNS_EINVAL, "null plan");
+    try {
+        std::string err;
+        const int rc = plan->store->add_edges(instance, src, dst, ts, eid, m, err);
+        if (rc != TNS_OK) g_err = err;
+        return rc;
+    } catch (const std::bad_alloc&) {
+        return fail(TNS_ENOMEM, "host allocation failed during ingestion");
+    }
+}
+
+int tns_commit(tns_plan* plan, void* hip_stream) {
+    g_err.clear();
+    if (!plan) return fail(TNS_EINVAL, "null plan");
+    DeviceGuard guard(plan->cfg.device);
+    if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the plan's device");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    tns::Store& s = *plan->store;
+    int rc;
+    // at least one element each, so that the kernels always get valid base pointers
+    if ((rc = ensure_capacity(plan->d_nodes, std::max<int64_t>(s.nodes.size(), 1), s.nodes, "allocating node table"))) return rc;
+    if ((rc = ensure_capacity(plan->d_blocks, std::max<int64_t>(s.blocks.size(), 1), s.blocks, "allocating block records"))) return rc;
+    if ((rc = ensure_capacity(plan->d_edges, std::max<int64_t>(s.edges.size(), 1), s.edges, "allocating edge data"))) return rc;
+    if ((rc = upload_dirty(plan->d_nodes, s.nodes, stream, "uploading node table"))) return rc;
+    if ((rc = upload_dirty(plan->d_blocks, s.blocks, stream, "uploading block records"))) return rc;
+    if ((rc = upload_dirty(plan->d_edges, s.edges, stream, "uploading edge data"))) return rc;
+    const hipError_t e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return fail_hip(e, "waiting for the upload");
+    s.nodes.clear_dirty();
+    s.blocks.clear_dirty();
+    s.edges.clear_dirty();
+    plan->committed = true;
+    return TNS_OK;
+}
+
+int tns_workspace(const tns_plan* plan, int64_t Q, size_t* bytes) {
+    g_err.clear();
+    if (!plan || !bytes || Q < 0) return fail(TNS_EINVAL, "null plan/pointer or negative Q");
+    *bytes = tns::compact_workspace_bytes(Q);
+    return TNS_OK;
+}
+
+static int check_compact_args(int64_t Q, const void* rowptr, const void* a, const void* b, const void* c,
+                              const void* ws, size_t ws_bytes) {
+    const int n_cmp = (a != nullptr) + (b != nullptr) + (c != nullptr);
+    if (!rowptr) return fail(TNS_EINVAL, "null d_rowptr");
+    if (Q > 0 && n_cmp != 3) return fail(TNS_EINVAL, "pass all four compaction outputs or none");
+    if (!ws) return fail(TNS_EINVAL, "compaction needs a workspace");
+    if (ws_bytes < tns::compact_workspace_bytes(Q)) return fail(TNS_ESIZE, "workspace smaller than tns_workspace()");
+    if (reinterpret_cast<uintptr_t>(ws) & 255) return fail(TNS_EINVAL, "workspace must be 256-byte aligned");
+    return TNS_OK;
+}
+
+static int fill_sample_args(tns_plan* plan, int64_t Q, const int32_t* d_targets, const float* d_t_start,
+                            const float* d_t_end, const int64_t* d_inst_rowptr, int64_t query_id_base,
+                            tns::SampleArgs& a) {
+    if (Q < 0) return fail(TNS_EINVAL, "negative Q");
+    if (!plan->committed) return fail(TNS_ESTATE, "tns_run before the first tns_commit");
+    if (Q > 0 && (!d_targets || !d_t_end)) return fail(TNS_EINVAL, "null query pointer");
+    if (plan->cfg.num_instances > 1 && !d_inst_rowptr) return fail(TNS_EINVAL, "d_inst_rowptr is required with several instances");
+    if (Q > (int64_t(1) << 36)) return fail(TNS_ESIZE, "more than 2^36 queries in one call: split the batch");
+    a = tns::SampleArgs{};
+    a.nodes = plan->d_nodes.ptr;
+    a.blocks = plan->d_blocks.ptr;
+    a.edges = plan->d_edges.ptr;
+    a.targets = d_targets;
+    a.t_start = d_t_start;
+    a.t_end = d_t_end;
+    a.inst_rowptr = plan->cfg.num_instances == 1 ? nullptr : d_inst_rowptr;
+    a.Q = Q;
+    a.num_nodes = plan->cfg.num_nodes;
+    a.num_blocks = plan->d_blocks.used;
+    a.qid_base = query_id_base;
+    a.seed = plan->cfg.seed;
+    a.num_instances = plan->cfg.num_instances;
+    a.fanout = plan->cfg.fanout;
+    a.policy = plan->cfg.policy;
+    a.inclusive_end = plan->cfg.inclusive_end;
+    a.xcd_remap = (plan->cfg.flags & TNS_FLAG_NO_XCD_REMAP) ? 0 : 1;
+    a.wide_offsets = plan->d_edges.used >= (int64_t(1) << 31) ? 1 : 0;
+    return TNS_OK;
+}
+
+static int run_compact(tns_plan* plan, int64_t Q, const int32_t* nbr, const int32_t* eid, const float* ts,
+                       const int32_t* count, int64_t* rowptr, int32_t* cn, int32_t* ce, float* ct, void* ws,
+                       hipStream_t stream) {
+    tns::CompactArgs c{};
+    c.nbr = nbr;
+    c.eid = eid;
+    c.ts = ts;
+    c.count = count;
+    c.rowptr = rowptr;
+    c.cmp_nbr = cn;
+    c.cmp_eid = ce;
+    c.cmp_ts = ct;
+    c.Q = Q;
+    c.fanout = plan->cfg.fanout;
+    c.workspace = ws;
+    const hipError_t e = tns::launch_compact(c, stream);
+    if (e != hipSuccess) return fail_hip(e, "launching the compaction kernels");
+    return TNS_OK;
+}
+
+int tns_run(tns_plan* plan, int64_t Q, const int32_t* d_targets, const float* d_t_start, const float* d_t_end,
+            const int64_t* d_inst_rowptr, int64_t query_id_base, int32_t* d_out_nbr, int32_t* d_out_eid,
+            float* d_out_ts, int32_t* d_out_count, int64_t* d_rowptr, int32_t* d_cmp_nbr, int32_t* d_cmp_eid,
+            float* d_cmp_ts, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+    g_err.clear();
+    if (!plan) return fail(TNS_EINVAL, "null plan");
+    tns::SampleArgs a;
+    int rc = fill_sample_args(plan, Q, d_targets, d_t_start, d_t_end, d_inst_rowptr, query_id_base, a);
+    if (rc) return rc;
+    if (Q > 0 && (!d_out_nbr || !d_out_eid || !d_out_ts || !d_out_count)) return fail(TNS_EINVAL, "null output pointer");
+    // compaction is requested by d_rowptr; with Q == 0 the dense arrays are empty and may be null
+    const bool want_cmp = d_rowptr != nullptr;
+    if (!want_cmp && (d_cmp_nbr || d_cmp_eid || d_cmp_ts)) return fail(TNS_EINVAL, "pass all four compaction outputs or none");
+    if (want_cmp && (rc = check_compact_args(Q, d_rowptr, d_cmp_nbr, d_cmp_eid, d_cmp_ts, d_workspace, workspace_bytes))) return rc;
+
+    DeviceGuard guard(plan->cfg.device);
+    if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the plan's device");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    a.out_nbr = d_out_nbr;
+    a.out_eid = d_out_eid;
+    a.out_ts = d_out_ts;
+    a.out_count = d_out_count;
+    const hipError_t e = tns::launch_sample(a, stream);
+    if (e != hipSuccess) return fail_hip(e, "launching the sampling kernel");
+    if (want_cmp)
+        return run_compact(plan, Q, d_out_nbr, d_out_eid, d_out_ts, d_out_count, d_rowptr, d_cmp_nbr, d_cmp_eid,
+                           d_cmp_ts, d_workspace, stream);
+    return TNS_OK;
+}
+
+int tns_compact(tns_plan* plan, int64_t Q, const int32_t* d_out_nbr, const int32_t* d_out_eid, const float* d_out_ts,
+                const int32_t* d_out_count, int64_t* d_rowptr, int32_t* d_cmp_nbr, int32_t* d_cmp_eid,
+                float* d_cmp_ts, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+    g_err.clear();
+    if (!plan) return fail(TNS_EINVAL, "null plan");
+    if (Q < 0) return fail(TNS_EINVAL, "negative Q");
+    if (Q > 0 && (!d_out_nbr || !d_out_eid || !d_out_ts || !d_out_count)) return fail(TNS_EINVAL, "null input pointer");
+    if (Q > (int64_t(1) << 36)) return fail(TNS_ESIZE, "more than 2^36 queries in one call: split the batch");
+    int rc = check_compact_args(Q, d_rowptr, d_cmp_nbr, d_cmp_eid, d_cmp_ts, d_workspace, workspace_bytes);
+    if (rc) return rc;
+    DeviceGuard guard(plan->cfg.device);
+    if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the plan's device");
+    return run_compact(plan, Q, d_out_nbr, d_out_eid, d_out_ts, d_out_count, d_rowptr, d_cmp_nbr, d_cmp_eid, d_cmp_ts,
+                       d_workspace, static_cast<hipStream_t>(hip_stream));
+}
+
+int tns_traffic_model(tns_plan* plan, int64_t Q, const int32_t* d_targets, const float* d_t_start,
+                      const float* d_t_end, const int64_t* d_inst_rowptr, int64_t query_id_base,
+                      uint64_t* d_counters, void* hip_stream) {
+    g_err.clear();
+    if (!plan) return fail(TNS_EINVAL, "null plan");
+    if (!d_counters) return fail(TNS_EINVAL, "null d_counters");
+    tns::SampleArgs a;
+    const int rc = fill_sample_args(plan, Q, d_targets, d_t_start, d_t_end, d_inst_rowptr, query_id_base, a);
+    if (rc) return rc;
+    DeviceGuard guard(plan->cfg.device);
+    if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the plan's device");
+    a.counters = reinterpret_cast<unsigned long long*>(d_counters);
+    const hipError_t e = tns::launch_sample(a, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail_hip(e, "launching the counting kernel");
+    return TNS_OK;
+}
+
+int tns_stats(const tns_plan* plan, int32_t instance, tns_stats_t* out) {
+    g_err.clear();
+    if (!plan || !out) return fail(TNS_EINVAL, "null plan or output");
+    const tns::Store& s = *plan->store;
+    const int32_t I = s.config().num_instances;
+    if (instance < -1 || instance >= I) return fail(TNS_ERANGE, "instance out of range");
+    const int32_t i0 = instance < 0 ? 0 : instance, i1 = instance < 0 ? I : instance + 1;
+    tns_stats_t r{};
+    for (int32_t i = i0; i < i1; ++i) {
+        const tns::InstanceTotals& t = s.totals(i);
+        r.num_blocks += t.blocks;
+        r.num_edges += t.edges;
+        r.wasted_slots += t.slots - t.edges;
+        r.edge_data_bytes += t.slots * (int64_t)sizeof(tns::Edge);
+        for (int64_t v = 0; v < s.config().num_nodes; ++v) {
+            const int64_t nb = s.nodes[s.node_index(i, v)].nblocks;
+            if (nb > r.max_list_len) r.max_list_len = nb;
+        }
+    }
+    const int64_t n_nodes = (int64_t)(i1 - i0) * s.config().num_nodes;
+    r.avg_list_len = n_nodes ? (double)r.num_blocks / (double)n_nodes : 0.0;
+    r.metadata_bytes = n_nodes * (int64_t)sizeof(tns::NodeRec) + r.num_blocks * (int64_t)sizeof(tns::BlockRec);
+    *out = r;
+    return TNS_OK;
+}
+
+int64_t tns_node_blocks(const tns_plan* plan, int32_t instance, int32_t node, int64_t max_blocks, int32_t* cap,
+                        int32_t* size, float* t_min, float* t_max) {
+    g_err.clear();
+    if (!plan) return fail(TNS_EINVAL, "null plan");
+    const tns::Store& s = *plan->store;
+    if (instance < 0 || instance >= s.config().num_instances || node < 0 || node >= s.config().num_nodes)
+        return fail(TNS_ERANGE, "instance or node out of range");
+    const int64_t nidx = s.node_index(instance, node);
+    int64_t n = 0;
+    for (int32_t b = s.head_of(nidx); b >= 0; b = s.blocks[b].next, ++n) {
+        if (n >= max_blocks) continue;
+        const tns::BlockRec& r = s.blocks[b];
+        if (cap) cap[n] = r.cap;
+        if (size) size[n] = r.size;
+        if (t_min) t_min[n] = r.t_min;
+        if (t_max) t_max[n] = r.t_max;
+    }
+    return n;
+}
+
+int tns_destroy(tns_plan* plan) {
+    g_err.clear();
+    if (!plan) return TNS_OK;
+    if (plan->d_nodes.ptr || plan->d_blocks.ptr || plan->d_edges.ptr) {
+        DeviceGuard guard(plan->cfg.device);
+        if (plan->d_nodes.ptr) (void)hipFree(plan->d_nodes.ptr);
+        if (plan->d_blocks.ptr) (void)hipFree(plan->d_blocks.ptr);
+        if (plan->d_edges.ptr) (void)hipFree(plan->d_edges.ptr);
+    }
+    delete plan;
+    return TNS_OK;
+}
+
+const char* tns_strerror(int status) {
+    switch (status) {
+        case TNS_OK: return "ok";
+        case TNS_EINVAL: return "invalid argument";
+        case TNS_EORDER: return "edges out of chronological order (or NaN timestamp)";
+        case TNS_ERANGE: return "node id or instance out of range";
+        case TNS_ENOMEM: return "out of memory";
+        case TNS_EHIP: return "HIP runtime error";
+        case TNS_ESTATE: return "store not committed";
+        case TNS_ESIZE: return "size beyond a limit or workspace too small";
+        default: return "unknown status";
+    }
+}
+
+const char* tns_last_error(void) { return g_err.c_str(); }
+
+}  // extern "C"

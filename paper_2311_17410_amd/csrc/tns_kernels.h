@@ -1,0 +1,65 @@
+// Launch interface between the C ABI (tns_api.hip) and the gfx950 kernels (tns_kernels.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstddef>
+#include <cstdint>
+
+#include "tns_layout.h"
+
+namespace tns {
+
+struct SampleArgs {
+    // store (device)
+    const NodeRec* nodes;
+    const BlockRec* blocks;
+    const Edge* edges;
+    // queries (device)
+    const int32_t* targets;
+    const float* t_start;        // may be null: -inf
+    const float* t_end;
+    const int64_t* inst_rowptr;  // may be null: one instance
+    // padded outputs (device)
+    int32_t* out_nbr;
+    int32_t* out_eid;
+    float* out_ts;
+    int32_t* out_count;
+    // non-null: count what the walk reads (node entries, block records, timestamp probes,
+    // edges selected) into counters[0..3] instead of producing outputs
+    unsigned long long* counters;
+    int64_t Q;
+    int64_t num_nodes;
+    int64_t num_blocks;  // block records on the device (walks never index past it)
+    int64_t qid_base;
+    uint64_t seed;
+    int32_t num_instances;
+    int32_t fanout;
+    int32_t policy;
+    int32_t inclusive_end;
+    int32_t xcd_remap;
+    int32_t wide_offsets;  // edge array has 2^31 or more entries: 64-bit positions in LDS
+};
+
+struct CompactArgs {
+    const int32_t* nbr;
+    const int32_t* eid;
+    const float* ts;
+    const int32_t* count;
+    int64_t* rowptr;
+    int32_t* cmp_nbr;
+    int32_t* cmp_eid;
+    float* cmp_ts;
+    int64_t Q;
+    int32_t fanout;
+    void* workspace;
+};
+
+constexpr int kCompactTile = 1024;  // queries per compaction tile
+
+size_t compact_workspace_bytes(int64_t Q);
+
+// Both only enqueue kernels on `stream`; they return the first launch error.
+hipError_t launch_sample(const SampleArgs& a, hipStream_t stream);
+hipError_t launch_compact(const CompactArgs& a, hipStream_t stream);
+
+}  // namespace tns

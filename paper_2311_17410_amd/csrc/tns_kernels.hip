@@ -1,0 +1,385 @@
+// gfx950 kernels: temporal neighbourhood sampling (Algorithm 1 of the paper, section 4.2) over
+// the block store of section 4.1, and removal of the padding (section 5).
+//
+// Thread mapping.  The paper runs one thread per sampled neighbour with the f threads of a
+// target adjacent.  On a 64-wide wavefront with dependent random reads (node entry -> block
+// record -> timestamps -> edge data) what limits throughput is the number of independent
+// chains in flight, so here the walk and the searches run one query per lane (64 independent
+// chains per wave), each lane leaves the edge positions it selected in LDS (the paper stages
+// candidate positions in shared memory for uniform sampling; here both policies do), and then
+// the whole wave gathers the edges and writes the padded rows cooperatively: lane l handles
+// flat slot it*64+l of the wave's 64*f slots, so every store instruction covers 256
+// consecutive bytes of each output array.
+#include "tns_kernels.h"
+
+#include <algorithm>
+
+namespace tns {
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kXcds = 8;
+
+// Workgroup -> tile mapping that gives each XCD (own L2) one contiguous range of tiles; the
+// hardware hands consecutive workgroup ids to the XCDs round-robin.
+__device__ __forceinline__ int64_t xcd_tile(int64_t bid, int64_t nb) {
+    const int64_t q = nb / kXcds, r = nb % kXcds;
+    const int64_t xcd = bid % kXcds, idx = bid / kXcds;
+    return xcd * q + (xcd < r ? xcd : r) + idx;
+}
+
+__device__ __forceinline__ uint32_t div_by(uint32_t s, uint32_t f, uint32_t magic) {
+    // floor(s / f) for s < 2^16 with magic = ceil(2^32 / f) (f >= 2)
+    return f == 1 ? s : __umulhi(s, magic);
+}
+
+// Rank in [0, c) for slot j of query qid: splitmix64 output function on the counter
+// seed + G * (qid * f + j + 1), top 32 bits scaled by multiply-shift.
+__device__ __forceinline__ uint64_t pick_rank(uint64_t seed, int64_t qid, int32_t f, int32_t j, uint64_t c) {
+    uint64_t z = seed + 0x9E3779B97F4A7C15ull * ((uint64_t)qid * (uint64_t)f + (uint64_t)j + 1ull);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return ((z >> 32) * c) >> 32;
+}
+
+// first index i in [0, n) with ts[i] >= x (STRICT=false) or ts[i] > x (STRICT=true)
+template <bool STRICT>
+__device__ __forceinline__ int32_t first_not_before(const Edge* __restrict__ e, int32_t n, float x, int32_t& probes) {
+    int32_t lo = 0, hi = n;
+    while (lo < hi) {
+        const int32_t mid = lo + ((hi - lo) >> 1);
+        const float t = e[mid].ts;
+        ++probes;
+        const bool ge = STRICT ? (t > x) : (t >= x);
+        if (ge) hi = mid; else lo = mid + 1;
+    }
+    return lo;
+}
+
+struct Window {
+    int32_t lo, hi;
+};
+
+// Candidate range [lo, hi) of one block for the window [tb, te) or [tb, te] (INCL).  The
+// block's t_min / t_max answer most cases without touching the edge data.
+template <bool INCL>
+__device__ __forceinline__ Window block_window(const BlockRec& r, const Edge* __restrict__ edges, float tb, float te,
+                                               int32_t& probes) {
+    Window w;
+    w.hi = r.size;
+    const bool all_before_end = INCL ? (te >= r.t_max) : (te > r.t_max);
+    if (!all_before_end) w.hi = first_not_before<INCL>(edges + r.off, r.size, te, probes);
+    w.lo = 0;
+    if (tb > r.t_min) w.lo = first_not_before<false>(edges + r.off, w.hi, tb, probes);
+    return w;
+}
+
+template <int POLICY, bool INCL, typename pos_t, bool COUNT>
+__global__ void __launch_bounds__(256) tns_sample_kernel(const SampleArgs p, const int32_t stride,
+                                                         const uint32_t f_magic) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    const int waves_per_wg = blockDim.x >> 6;
+    pos_t* __restrict__ s_pos = reinterpret_cast<pos_t*>(smem) + (size_t)wave * kWave * stride + (size_t)lane * stride;
+
+    const int64_t tile = p.xcd_remap ? xcd_tile(blockIdx.x, gridDim.x) : (int64_t)blockIdx.x;
+    const int64_t q0 = (tile * waves_per_wg + wave) * kWave;
+    const int64_t q = q0 + lane;
+    const int32_t f = p.fanout;
+
+    int32_t k = 0;
+    int32_t n_nodes = 0, n_blocks = 0, n_probes = 0;   // traffic model counters (COUNT only)
+    if (q < p.Q) {
+        const int32_t v = p.targets[q];
+        const float te = p.t_end[q];
+        const float tb = p.t_start ? p.t_start[q] : -INFINITY;
+        int64_t nbase = 0;
+        bool ok = (uint32_t)v < (uint64_t)p.num_nodes && !(te != te) && !(tb != tb);
+        if (p.inst_rowptr) {
+            // instance b owns queries inst_rowptr[b] .. inst_rowptr[b+1]-1
+            int32_t lo = 0, hi = p.num_instances;
+            while (lo < hi) {
+                const int32_t mid = lo + ((hi - lo) >> 1);
+                if (p.inst_rowptr[mid + 1] <= q) lo = mid + 1; else hi = mid;
+            }
+            ok = ok && lo < p.num_instances;
+            nbase = (int64_t)lo * p.num_nodes;
+        }
+        if (ok) {
+            const NodeRec nd = p.nodes[nbase + v];
+            ++n_nodes;
+            int32_t b = (nd.flags & 1) ? -1 : nd.tail;
+            if (POLICY == 0) {
+                for (int32_t it = 0; it < nd.nblocks && b >= 0 && (int64_t)b < p.num_blocks && k < f; ++it) {
+                    const BlockRec r = p.blocks[b];
+                    ++n_blocks;
+                    if (INCL ? (te < r.t_min) : (te <= r.t_min)) { b = r.prev; continue; }   // block is after the window
+                    if (tb > r.t_max) break;                                                 // block is before the window
+                    const Window w = block_window<INCL>(r, p.edges, tb, te, n_probes);
+                    const int32_t take = min(f - k, w.hi - w.lo);
+                    for (int32_t j = 0; j < take; ++j) s_pos[k + j] = (pos_t)(r.off + w.hi - 1 - j);
+                    k += take > 0 ? take : 0;
+                    if (w.lo > 0) break;          // everything older is before the window
+                    b = r.prev;
+                }
+            } else {
+                // pass 1: all overlapping blocks; total candidates c; the newest f positions are
+                // recorded on the way (they are the answer when c <= f)
+                int64_t c = 0;
+                int32_t b_first = -1, hi_first = 0, b_last = -1, lo_last = 0;
+                for (int32_t it = 0; it < nd.nblocks && b >= 0 && (int64_t)b < p.num_blocks; ++it) {
+                    const BlockRec r = p.blocks[b];
+                    ++n_blocks;
+                    if (INCL ? (te < r.t_min) : (te <= r.t_min)) { b = r.prev; continue; }
+                    if (tb > r.t_max) break;
+                    const Window w = block_window<INCL>(r, p.edges, tb, te, n_probes);
+                    const int32_t cnt = w.hi - w.lo;
+                    if (cnt > 0) {
+                        if (b_first < 0) { b_first = b; hi_first = w.hi; }
+                        b_last = b; lo_last = w.lo;
+                        const int32_t take = min(f - k, cnt);
+                        for (int32_t j = 0; j < take; ++j) s_pos[k + j] = (pos_t)(r.off + w.hi - 1 - j);
+                        k += take > 0 ? take : 0;
+                        c += cnt;
+                    }
+                    if (w.lo > 0) break;
+                    b = r.prev;
+                }
+                if (c > (int64_t)f) {
+                    // f independent picks; rank counted from the oldest candidate, turned into a
+                    // distance from the newest one; unresolved entries are stored negative
+                    const int64_t qid = p.qid_base + q;
+                    for (int32_t j = 0; j < f; ++j) {
+                        const int64_t from_newest = c - 1 - (int64_t)pick_rank(p.seed, qid, f, j, (uint64_t)c);
+                        s_pos[j] = (pos_t)(-(from_newest + 1));
+                    }
+                    // pass 2: walk the overlapping blocks again and resolve rank -> position
+                    int64_t cum = 0;
+                    b = b_first;
+                    for (int32_t it = 0; it < nd.nblocks && b >= 0 && (int64_t)b < p.num_blocks; ++it) {
+                        const BlockRec r = p.blocks[b];
+                    ++n_blocks;
+                        const int32_t hi = (b == b_first) ? hi_first : r.size;
+                        const int32_t lo = (b == b_last) ? lo_last : 0;
+                        const int64_t cnt = hi - lo;
+                        for (int32_t j = 0; j < f; ++j) {
+                            const int64_t sv = (int64_t)s_pos[j];
+                            if (sv < 0) {
+                                const int64_t rr = -(sv + 1) - cum;
+                                if (rr < cnt) s_pos[j] = (pos_t)(r.off + hi - 1 - rr);
+                            }
+                        }
+                        cum += cnt;
+                        if (b == b_last) break;
+                        b = r.prev;
+                    }
+                }
+            }
+        }
+    }
+    if (COUNT) {
+        // totals of what this launch reads: node entries, block records, timestamp probes, edges
+        unsigned long long v4[4] = {(unsigned long long)n_nodes, (unsigned long long)n_blocks,
+                                    (unsigned long long)n_probes, (unsigned long long)k};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            unsigned long long v = v4[i];
+            for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, kWave);
+            if (lane == 0 && v) atomicAdd(&p.counters[i], v);
+        }
+        return;
+    }
+    __syncthreads();
+
+    // cooperative gather + padded write: the wave's 64*f slots in flat order
+    const pos_t* __restrict__ w_pos = reinterpret_cast<const pos_t*>(smem) + (size_t)wave * kWave * stride;
+    const int64_t out0 = q0 * f;
+    for (int32_t it = 0; it < f; ++it) {
+        const uint32_t s = (uint32_t)(it * kWave + lane);
+        const uint32_t ql = div_by(s, (uint32_t)f, f_magic);
+        const int32_t j = (int32_t)(s - ql * (uint32_t)f);
+        const int32_t kq = __shfl(k, (int)ql, kWave);
+        if (q0 + (int64_t)ql < p.Q) {
+            int32_t nbr = -1, eid = -1;
+            float t = 0.0f;
+            if (j < kq) {
+                const int64_t pos = (int64_t)w_pos[ql * stride + j];
+                const Edge e = p.edges[pos];
+                nbr = e.nbr; eid = e.eid; t = e.ts;
+            }
+            p.out_nbr[out0 + s] = nbr;
+            p.out_eid[out0 + s] = eid;
+            p.out_ts[out0 + s] = t;
+        }
+    }
+    if (q < p.Q) p.out_count[q] = k;
+}
+
+// ---- padding removal -------------------------------------------------------------------
+
+__device__ __forceinline__ int32_t wave_inclusive_scan(int32_t v, int lane) {
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int32_t u = __shfl_up(v, d, kWave);
+        if (lane >= d) v += u;
+    }
+    return v;
+}
+
+// sum of counts per tile of kCompactTile queries
+__global__ void __launch_bounds__(256) tns_count_tile_sums(const int32_t* __restrict__ count, int64_t Q,
+                                                           int32_t* __restrict__ tile_sums) {
+    __shared__ int32_t s_w[4];
+    const int64_t base = (int64_t)blockIdx.x * kCompactTile;
+    int32_t v = 0;
+#pragma unroll
+    for (int i = 0; i < kCompactTile / 256; ++i) {
+        const int64_t q = base + i * 256 + threadIdx.x;
+        if (q < Q) v += count[q];
+    }
+    const int lane = threadIdx.x & 63;
+    v = wave_inclusive_scan(v, lane);
+    if (lane == 63) s_w[threadIdx.x >> 6] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) tile_sums[blockIdx.x] = s_w[0] + s_w[1] + s_w[2] + s_w[3];
+}
+
+// exclusive scan of the tile sums (int64), one workgroup; also writes rowptr[Q]
+__global__ void __launch_bounds__(1024) tns_scan_tile_sums(const int32_t* __restrict__ tile_sums, int64_t num_tiles,
+                                                           int64_t* __restrict__ tile_offs, int64_t* __restrict__ total) {
+    __shared__ int32_t s_w[16];
+    __shared__ int64_t s_carry;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (threadIdx.x == 0) s_carry = 0;
+    __syncthreads();
+    for (int64_t base = 0; base < num_tiles; base += 1024) {
+        const int64_t i = base + threadIdx.x;
+        const int32_t v = i < num_tiles ? tile_sums[i] : 0;
+        const int32_t inc = wave_inclusive_scan(v, lane);
+        if (lane == 63) s_w[wave] = inc;
+        __syncthreads();
+        int32_t wave_off = 0, all = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            const int32_t t = s_w[w];
+            if (w < wave) wave_off += t;
+            all += t;
+        }
+        const int64_t carry = s_carry;
+        if (i < num_tiles) tile_offs[i] = carry + wave_off + (inc - v);
+        __syncthreads();
+        if (threadIdx.x == 0) s_carry = carry + all;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *total = s_carry;
+}
+
+// rowptr of the tile's queries and scatter of the filled slots to the dense arrays
+__global__ void __launch_bounds__(256) tns_compact_scatter(const CompactArgs a, const int64_t* __restrict__ tile_offs,
+                                                           const uint32_t f_magic) {
+    __shared__ int32_t s_excl[kCompactTile];
+    __shared__ int32_t s_cnt[kCompactTile];
+    __shared__ int32_t s_w[4];
+    constexpr int kPer = kCompactTile / 256;
+    const int64_t base = (int64_t)blockIdx.x * kCompactTile;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int32_t c[kPer];
+    int32_t sum = 0;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        const int64_t q = base + threadIdx.x * kPer + i;
+        c[i] = q < a.Q ? a.count[q] : 0;
+        sum += c[i];
+    }
+    const int32_t inc = wave_inclusive_scan(sum, lane);
+    if (lane == 63) s_w[wave] = inc;
+    __syncthreads();
+    int32_t excl = inc - sum;
+    for (int w = 0; w < wave; ++w) excl += s_w[w];
+    const int64_t tile_off = tile_offs[blockIdx.x];
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        const int ql = threadIdx.x * kPer + i;
+        s_excl[ql] = excl;
+        s_cnt[ql] = c[i];
+        if (base + ql < a.Q) a.rowptr[base + ql] = tile_off + excl;
+        excl += c[i];
+    }
+    __syncthreads();
+    if (!a.cmp_nbr) return;
+    const uint32_t f = (uint32_t)a.fanout;
+    const uint32_t slots = kCompactTile * f;
+    const int64_t in0 = base * f;
+    const int64_t in_end = a.Q * (int64_t)f;
+    for (uint32_t s = threadIdx.x; s < slots; s += 256) {
+        if (in0 + s >= in_end) break;
+        const uint32_t ql = div_by(s, f, f_magic);
+        const uint32_t j = s - ql * f;
+        if ((int32_t)j < s_cnt[ql]) {
+            const int64_t d = tile_off + s_excl[ql] + j;
+            a.cmp_nbr[d] = a.nbr[in0 + s];
+            a.cmp_eid[d] = a.eid[in0 + s];
+            a.cmp_ts[d] = a.ts[in0 + s];
+        }
+    }
+}
+
+inline uint32_t magic_for(int32_t f) { return f <= 1 ? 0u : (uint32_t)(((uint64_t(1) << 32) + (uint64_t)f - 1) / (uint64_t)f); }
+
+template <int POLICY, bool INCL, typename pos_t, bool COUNT>
+hipError_t launch_sample_t(const SampleArgs& a, hipStream_t stream) {
+    const int32_t stride = a.fanout | 1;                                    // odd: conflict-free per-lane rows
+    const size_t per_wave = (size_t)kWave * stride * sizeof(pos_t);
+    int waves = (int)std::min<size_t>(4, std::max<size_t>(1, (48u << 10) / per_wave));
+    const int64_t per_wg = (int64_t)waves * kWave;
+    const int64_t grid = (a.Q + per_wg - 1) / per_wg;
+    if (grid <= 0) return hipSuccess;
+    if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((tns_sample_kernel<POLICY, INCL, pos_t, COUNT>), dim3((unsigned)grid), dim3(waves * kWave),
+                       per_wave * waves, stream, a, stride, magic_for(a.fanout));
+    return hipGetLastError();
+}
+
+}  // namespace
+
+size_t compact_workspace_bytes(int64_t Q) {
+    const int64_t tiles = (Q + kCompactTile - 1) / kCompactTile;
+    const size_t sums = ((size_t)tiles * sizeof(int32_t) + 255) & ~size_t(255);
+    const size_t offs = ((size_t)tiles * sizeof(int64_t) + 255) & ~size_t(255);
+    return sums + offs + 256;
+}
+
+hipError_t launch_sample(const SampleArgs& a, hipStream_t stream) {
+    const bool incl = a.inclusive_end != 0;
+    const bool wide = a.wide_offsets != 0;
+#define TNS_DISPATCH(POL, CNT)                                                          \
+    (incl ? (wide ? launch_sample_t<POL, true, int64_t, CNT>(a, stream)                 \
+                  : launch_sample_t<POL, true, int32_t, CNT>(a, stream))                \
+          : (wide ? launch_sample_t<POL, false, int64_t, CNT>(a, stream)                \
+                  : launch_sample_t<POL, false, int32_t, CNT>(a, stream)))
+    if (a.counters) return a.policy == 0 ? TNS_DISPATCH(0, true) : TNS_DISPATCH(1, true);
+    return a.policy == 0 ? TNS_DISPATCH(0, false) : TNS_DISPATCH(1, false);
+#undef TNS_DISPATCH
+}
+
+hipError_t launch_compact(const CompactArgs& a, hipStream_t stream) {
+    const int64_t tiles = (a.Q + kCompactTile - 1) / kCompactTile;
+    unsigned char* ws = static_cast<unsigned char*>(a.workspace);
+    int32_t* sums = reinterpret_cast<int32_t*>(ws);
+    const size_t sums_bytes = ((size_t)tiles * sizeof(int32_t) + 255) & ~size_t(255);
+    int64_t* offs = reinterpret_cast<int64_t*>(ws + sums_bytes);
+    if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (tiles > 0) {
+        hipLaunchKernelGGL(tns_count_tile_sums, dim3((unsigned)tiles), dim3(256), 0, stream, a.count, a.Q, sums);
+    }
+    hipLaunchKernelGGL(tns_scan_tile_sums, dim3(1), dim3(1024), 0, stream, sums, tiles, offs, a.rowptr + a.Q);
+    if (tiles > 0) {
+        hipLaunchKernelGGL(tns_compact_scatter, dim3((unsigned)tiles), dim3(256), 0, stream, a, offs,
+                           magic_for(a.fanout));
+    }
+    return hipGetLastError();
+}
+
+}  // namespace tns

@@ -1,0 +1,188 @@
+"""GPU parity: the HIP library, called through the C ABI binding, against the CPU oracle on
+the same seeded inputs.  Every output array must match bit for bit (ids, counts, offsets
+are integers; timestamps are copied fp32 values; no arithmetic produces a rounded float)."""
+import numpy as np
+import pytest
+
+from paper_2311_17410_amd import workloads as W
+from _harness import assert_same, build_plan, gpu_sample, oracle_sample
+from conftest import progress
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2311_17410_amd import binding
+    binding.lib()          # fails loudly if the HIP library is not built
+    return binding
+
+
+def wl_of(stream, name="tiny", fanout=10, tau=48):
+    return W.Workload(name, 0, [stream], fanout=fanout, tau=tau)
+
+
+# ---- small cases: ties, every option, sizes that span tiles with a ragged tail ---------------
+
+@pytest.mark.parametrize("policy", [0, 1])
+@pytest.mark.parametrize("inclusive", [0, 1])
+@pytest.mark.parametrize("f", [1, 2, 10, 25, 64])
+def test_tiny_streams_all_options(B, oracle_lib, policy, inclusive, f):
+    st = W.tiny_stream(41, 3000, 23, 256, ties=True)
+    wl = wl_of(st, fanout=f)
+    targets, t_start, t_end = W.random_queries(42, st, 1000 + 37)      # ragged: not a multiple of 64
+    for tau, sizing, batch in [(48, 0, 256), (1, 0, 7), (4, 2, 3000), (8192, 1, 375)]:
+        plan = build_plan(B, wl, policy, inclusive, seed=3, tau=tau, sizing=sizing, batch=batch)
+        for tb in (t_start, None):
+            got = gpu_sample(plan, targets, tb, t_end)
+            ref = oracle_sample(oracle_lib, wl, targets, tb, t_end, None, f, policy, inclusive, 3)
+            assert_same(got, ref, oracle_lib, f"tau={tau} sizing={sizing} batch={batch} start={'y' if tb is not None else 'n'}")
+        # stream-derived queries (query i = event i)
+        got = gpu_sample(plan, st.src, None, st.ts)
+        ref = oracle_sample(oracle_lib, wl, st.src, None, st.ts, None, f, policy, inclusive, 3)
+        assert_same(got, ref, oracle_lib, "self queries")
+        plan.close()
+
+
+def test_no_ties_long_lists_one_edge_per_batch(B, oracle_lib):
+    st = W.tiny_stream(7, 700, 3, 1, ties=False)          # one edge per batch: longest possible lists
+    wl = wl_of(st, fanout=10, tau=8)
+    targets, t_start, t_end = W.random_queries(8, st, 513)
+    for policy in (0, 1):
+        plan = build_plan(B, wl, policy, 0, seed=11)
+        assert plan.stats()["max_list_len"] > 20
+        for tb in (t_start, None):
+            got = gpu_sample(plan, targets, tb, t_end)
+            ref = oracle_sample(oracle_lib, wl, targets, tb, t_end, None, 10, policy, 0, 11)
+            assert_same(got, ref, oracle_lib, f"policy={policy}")
+        plan.close()
+
+
+def test_edge_cases(B, oracle_lib):
+    import torch
+    st = W.tiny_stream(5, 200, 6, 32)
+    wl = wl_of(st, fanout=4)
+    plan = build_plan(B, wl)
+    # empty query batch: nothing launched that touches memory, rowptr = [0]
+    got = gpu_sample(plan, np.array([], np.int32), None, np.array([], np.float32))
+    assert got["count"].shape == (0,) and list(got["rowptr"]) == [0]
+    # out-of-range ids, NaN and infinite bounds
+    targets = np.array([-1, 6, 0, 0, 0, 0, 5, 2147483647, -2147483648], np.int32)
+    t_end = np.array([1, 1, np.nan, np.inf, -np.inf, 10, 10, 10, 10], np.float32)
+    t_start = np.array([0, 0, 0, -np.inf, -np.inf, np.nan, np.inf, 0, 0], np.float32)
+    got = gpu_sample(plan, targets, t_start, t_end)
+    ref = oracle_sample(oracle_lib, wl, targets, t_start, t_end, None, 4, 0, 0, 0)
+    assert_same(got, ref, oracle_lib, "odd queries")
+    assert list(got["count"][[0, 1, 2, 4, 5, 6, 7, 8]]) == [0] * 8
+    # without compaction outputs
+    got = gpu_sample(plan, targets, t_start, t_end, compact=False)
+    assert_same(got, ref, None, "no compaction")
+    plan.close()
+    # a store with no edges at all
+    empty = W.Workload("empty", 0, [W.Stream(5, np.array([], np.int32), np.array([], np.int32), np.array([], np.float32), 8)], fanout=3)
+    plan = build_plan(B, empty)
+    got = gpu_sample(plan, np.array([0, 4, 9], np.int32), None, np.array([1, 2, 3], np.float32))
+    assert np.all(got["count"] == 0) and np.all(got["nbr"] == -1) and list(got["rowptr"]) == [0, 0, 0, 0]
+    plan.close()
+    # argument errors are reported, nothing is launched
+    plan = build_plan(B, wl)
+    t = torch.zeros(8, dtype=torch.int32, device="cuda")
+    with pytest.raises(B.TnsError) as ei:
+        B.tns_run(plan.handle, 2, t.data_ptr(), 0, t.data_ptr(), 0, 0, t.data_ptr(), t.data_ptr(), t.data_ptr(), 0)
+    assert ei.value.status == B.TNS_EINVAL
+    with pytest.raises(B.TnsError) as ei:
+        B.tns_run(plan.handle, 2, t.data_ptr(), 0, t.data_ptr(), 0, 0, t.data_ptr(), t.data_ptr(), t.data_ptr(),
+                  t.data_ptr(), t.data_ptr(), t.data_ptr(), t.data_ptr(), t.data_ptr(), t.data_ptr(), 8)
+    assert ei.value.status == B.TNS_ESIZE
+    plan.close()
+
+
+def test_incremental_commit(B, oracle_lib):
+    st = W.tiny_stream(61, 4000, 40, 500, ties=True)
+    wl = wl_of(st, fanout=10, tau=16)
+    plan = B.Plan(st.num_nodes, 10, block_threshold=16)
+    targets, t_start, t_end = W.random_queries(62, st, 777)
+    for upto in (500, 1500, 4000):
+        lo = 0 if upto == 500 else (500 if upto == 1500 else 1500)
+        for a in range(lo, upto, 500):
+            B.tns_add_edges(plan.handle, 0, st.src[a:a + 500], st.dst[a:a + 500], st.ts[a:a + 500])
+        before = gpu_sample(plan, targets, t_start, t_end) if upto > 500 else None
+        plan.commit()
+        part = W.Workload("part", 0, [W.Stream(st.num_nodes, st.src[:upto], st.dst[:upto], st.ts[:upto], 500)], fanout=10, tau=16)
+        ref = oracle_sample(oracle_lib, part, targets, t_start, t_end, None, 10, 0, 0, 0)
+        assert_same(gpu_sample(plan, targets, t_start, t_end), ref, oracle_lib, f"after commit of {upto}")
+        if before is not None:      # uncommitted edges were not visible
+            assert_same(before, prev_ref, oracle_lib, "snapshot semantics")
+        prev_ref = ref
+    plan.close()
+
+
+def test_query_id_base_and_chunked_runs(B, oracle_lib):
+    st = W.tiny_stream(71, 5000, 5, 512, ties=False)
+    wl = wl_of(st, fanout=6)
+    plan = build_plan(B, wl, policy=1, seed=77)
+    ref = oracle_sample(oracle_lib, wl, st.src, None, st.ts, None, 6, 1, 0, 77)
+    whole = gpu_sample(plan, st.src, None, st.ts)
+    assert_same(whole, ref, oracle_lib, "whole")
+    cut = 2111
+    a = gpu_sample(plan, st.src[:cut], None, st.ts[:cut], compact=False)
+    b = gpu_sample(plan, st.src[cut:], None, st.ts[cut:], compact=False, query_id_base=cut)
+    assert np.array_equal(np.concatenate([a["eid"], b["eid"]]), ref.eid)
+    plan.close()
+
+
+# ---- the configurations --------------------------------------------------------------------
+
+def _check_config(B, oracle, wl, threads=16, window=True, policies=(0, 1)):
+    targets, t_start, t_end, rowptr = wl.queries(window_frac=0.25)
+    rp = rowptr if wl.num_instances > 1 else None
+    adjs = [oracle.Adjacency(st.num_nodes, st.src, st.dst, st.ts) for st in wl.streams]
+    for policy in policies:
+        plan = build_plan(B, wl, policy, 0, seed=wl.seed)
+        for tb in ((None, t_start) if window else (None,)):
+            progress(f"{wl.name} policy={policy} windowed={tb is not None}")
+            got = gpu_sample(plan, targets, tb, t_end, rp)
+            ref = oracle_sample(oracle, wl, targets, tb, t_end, rp, wl.fanout, policy, 0, wl.seed, threads=threads, adjs=adjs)
+            assert_same(got, ref, oracle, f"{wl.name} policy={policy}")
+        plan.close()
+    for a in adjs:
+        a.close()
+
+
+def test_c1(B, oracle_lib):
+    _check_config(B, oracle_lib, W.c1())
+
+
+def test_c1_literal_id_range(B, oracle_lib):
+    _check_config(B, oracle_lib, W.literal_range("C1"))
+
+
+def test_c2(B, oracle_lib):
+    _check_config(B, oracle_lib, W.c2())
+
+
+def test_c2_literal_id_range(B, oracle_lib):
+    _check_config(B, oracle_lib, W.literal_range("C2"), window=False)
+
+
+def test_c2_inclusive_and_no_remap(B, oracle_lib):
+    wl = W.c2()
+    targets, _, t_end, _ = wl.queries()
+    for incl, flags in ((1, 0), (0, B.TNS_FLAG_NO_XCD_REMAP)):
+        plan = build_plan(B, wl, 0, incl, flags=flags)
+        got = gpu_sample(plan, targets, None, t_end)
+        ref = oracle_sample(oracle_lib, wl, targets, None, t_end, None, wl.fanout, 0, incl, 0, threads=16)
+        assert_same(got, ref, oracle_lib, f"incl={incl} flags={flags}")
+        plan.close()
+
+
+def test_c3_zipf_hub(B, oracle_lib):
+    progress("generating C3")
+    _check_config(B, oracle_lib, W.c3())
+
+
+def test_c4_batched_instances(B, oracle_lib):
+    progress("generating C4")
+    _check_config(B, oracle_lib, W.c4())

@@ -1,0 +1,228 @@
+#!/usr/bin/env python3
+"""Bench of the sampling hot path on one MI355X.
+
+A step is one pass of the whole path over one query batch: sampling kernel (node lookup,
+block walk, in-block search, selection, padded write) followed by padding removal, on
+inputs already resident in HBM.  Prints ONE JSON line (see the design doc for the byte model
+behind `roofline`).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C5] [--policy recent]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+
+
+def log(msg: str) -> None:
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
+def measured_traffic(workload: str, policy: str):
+    """HBM bytes per launch of the sampling kernel from the committed rocprofv3 counter runs
+    (profiles/traffic.json, written by hand from the --pmc summaries); None if not measured."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as fh:
+            return json.load(fh).get(f"{workload}:{policy}")
+    except OSError:
+        return None
+
+
+def cpu_baseline(wl, policy: int, seed: int, target_seconds: float, d_out, torch):
+    """The CPU oracle as it stands, on a strided sample of the same query batch, all host cores
+    the box grants.  Also compares the sampled rows with the GPU result."""
+    import numpy as np
+    import oracle
+    st = wl.streams[0]
+    threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or min(os.cpu_count() or 1, 16)
+    log(f"cpu_baseline: building the oracle's per-node lists over {st.n} edges")
+    t0 = time.time()
+    adj = oracle.Adjacency(st.num_nodes, st.src, st.dst, st.ts)
+    build_s = time.time() - t0
+    chunk = 1 << 20
+    stride = 1
+    done, spent, used, ok = 0, 0.0, threads, True
+    pos = 0
+    f = wl.fanout
+    while spent < target_seconds and pos < st.n:
+        sel = np.arange(pos, min(pos + chunk * stride, st.n), stride, dtype=np.int64)
+        tg, te = st.src[sel], st.ts[sel]
+        t0 = time.time()
+        ref = adj.sample(tg, None, te, f, policy=policy, seed=seed, q_ids=sel, threads=threads)
+        spent += time.time() - t0
+        used = adj.threads_used
+        if done == 0:          # parity of the sample against what the GPU wrote for the same queries
+            idx = torch.from_numpy(sel).to(d_out["count"].device)
+            g_eid = d_out["eid"].view(-1, f).index_select(0, idx).cpu().numpy()
+            g_cnt = d_out["count"].index_select(0, idx).cpu().numpy()
+            ok = bool(np.array_equal(g_eid, ref.eid) and np.array_equal(g_cnt, ref.count))
+        done += len(sel)
+        pos += chunk * stride
+    adj.close()
+    return {"value": done / spent, "unit": "elements/s", "cores": used, "kind": "oracle",
+            "sample": f"every {stride}th query of the batch from query 0 on, {done} queries, {spent:.1f} s "
+                      f"(per-node list build {build_s:.1f} s not included)",
+            "matches_gpu_on_sample": ok}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C5", help="C1..C5 (C5 = the headline: n = 2^28)")
+    ap.add_argument("--log2n", type=int, default=None, help="override the stream length of C3/C5 (experiments)")
+    ap.add_argument("--policy", default="recent", choices=["recent", "uniform"])
+    ap.add_argument("--windowed", action="store_true", help="t_start = t_end - 0.25 span instead of -inf")
+    ap.add_argument("--no-remap", action="store_true", help="disable the XCD-aware tile mapping")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (torch copy_) so that rocprofv3 counter runs of this "
+                         "command contain a kernel of known traffic")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU oracle time budget (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2311_17410_amd import binding as B
+    from paper_2311_17410_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    B.lib()
+    dev = torch.device("cuda", 0)
+    policy = B.TNS_POLICY_RECENT if args.policy == "recent" else B.TNS_POLICY_UNIFORM
+
+    kw = {}
+    if args.log2n is not None and args.workload.upper() in ("C3", "C5"):
+        kw["log2_n"] = args.log2n
+    log(f"generating {args.workload} {kw or ''}")
+    wl = W.by_name(args.workload, **kw)
+    Q, f = wl.total_edges, wl.fanout
+
+    log(f"ingesting {Q} edges into {wl.num_instances} instance(s), tau={wl.tau}")
+    t0 = time.time()
+    plan = B.Plan(wl.num_nodes, f, policy=policy, block_threshold=wl.tau, num_instances=wl.num_instances,
+                  seed=wl.seed, flags=B.TNS_FLAG_NO_XCD_REMAP if args.no_remap else 0)
+    last = time.time()
+    for i, st in enumerate(wl.streams):
+        for lo, hi in st.batches():
+            B.tns_add_edges(plan.handle, i, st.src[lo:hi], st.dst[lo:hi], st.ts[lo:hi], None)
+            if time.time() - last > 20:
+                log(f"  instance {i}: {hi}/{st.n} edges")
+                last = time.time()
+    ingest_s = time.time() - t0
+    t0 = time.time()
+    plan.commit()
+    commit_s = time.time() - t0
+    stats = plan.stats()
+    log(f"store: {stats['num_blocks']} blocks, avg list {stats['avg_list_len']:.2f}, max {stats['max_list_len']}, "
+        f"edge data {stats['edge_data_bytes'] / 2**30:.2f} GiB, metadata {stats['metadata_bytes'] / 2**30:.2f} GiB "
+        f"(ingest {ingest_s:.1f} s, commit {commit_s:.1f} s)")
+
+    targets, t_start, t_end, rowptr = wl.queries(window_frac=0.25 if args.windowed else None)
+    d_targets = torch.from_numpy(targets).to(dev)
+    d_te = torch.from_numpy(t_end).to(dev)
+    d_tb = None if t_start is None else torch.from_numpy(t_start).to(dev)
+    d_rp = torch.from_numpy(rowptr).to(dev) if wl.num_instances > 1 else None
+    out = plan.alloc_outputs(Q, compact=True)
+    p = lambda t: 0 if t is None else t.data_ptr()
+    stream = torch.cuda.current_stream().cuda_stream
+    ws_bytes = out["workspace"].numel()
+
+    def sample():
+        B.tns_run(plan.handle, Q, p(d_targets), p(d_tb), p(d_te), p(d_rp), 0, p(out["nbr"]), p(out["eid"]),
+                  p(out["ts"]), p(out["count"]), hip_stream=stream)
+
+    def compact():
+        B.tns_compact(plan.handle, Q, p(out["nbr"]), p(out["eid"]), p(out["ts"]), p(out["count"]), p(out["rowptr"]),
+                      p(out["cmp_nbr"]), p(out["cmp_eid"]), p(out["cmp_ts"]), p(out["workspace"]), ws_bytes, stream)
+
+    # byte model: what the walk reads, counted by the library's own counting pass
+    counters = torch.zeros(4, dtype=torch.int64, device=dev)
+    B.tns_traffic_model(plan.handle, Q, p(d_targets), p(d_tb), p(d_te), p(d_rp), 0, counters.data_ptr(), stream)
+    torch.cuda.synchronize()
+    n_nodes, n_blocks, n_probes, n_edges = (int(x) for x in counters.cpu())
+    q_in = 8 + (4 if d_tb is not None else 0) + (0 if d_rp is None else 0)
+    bytes_sample = {"queries": q_in * Q, "node_entries": 16 * n_nodes, "block_records": 32 * n_blocks,
+                    "timestamp_probes": 4 * n_probes, "edge_gather": 12 * n_edges, "padded_write": (12 * f + 4) * Q}
+    alg_sample = sum(bytes_sample.values())
+    alg_compact = (4 + 4 + 12 * f) * Q + 8 * (Q + 1) + 12 * n_edges     # counts twice, padded once, rowptr, dense
+
+    log(f"warm-up {args.warmup}, timing {args.steps} steps")
+    for _ in range(args.warmup):
+        sample()
+        compact()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        ev[k][0].record()
+        sample()
+        ev[k][1].record()
+        compact()
+        ev[k][2].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_sample = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
+    ms_compact = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
+    if args.calibrate_copy:
+        a = torch.arange(1 << 28, dtype=torch.int32, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+    total_k = int(out["rowptr"][-1].item())
+    assert total_k == n_edges, (total_k, n_edges)
+
+    achieved = alg_sample / (ms_sample * 1e-3) / 1e9
+    result = {
+        "metric": "hot-path elements/sec at 1 MI355X + % of HBM/MFMA roofline",
+        "value": Q / (ms_per_step * 1e-3),
+        "unit": "elements/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32 ids / fp32 timestamps (copied and compared, no arithmetic)",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {wl.description}; query i = (src[i], -inf, ts[i]); f={f}, tau={wl.tau}, "
+                               f"policy={args.policy}, window={'0.25 span' if args.windowed else 'unbounded'}",
+                   "queries": Q, "instances": wl.num_instances, "nodes_per_instance": wl.num_nodes,
+                   "xcd_remap": not args.no_remap},
+        "roofline": {"bound": "hbm", "kernel": "tns_sample_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": measured_traffic(wl.name, args.policy),
+                     "algorithmic_bytes_per_launch": alg_sample, "bytes_breakdown": bytes_sample,
+                     "ms_per_launch": ms_sample},
+        "compaction": {"ms_per_step": ms_compact, "algorithmic_bytes": alg_compact,
+                       "achieved_GBs": alg_compact / (ms_compact * 1e-3) / 1e9},
+        "sampled_edges_per_s": total_k / (ms_per_step * 1e-3),
+        "per_query": {"block_records": n_blocks / Q, "timestamp_probes": n_probes / Q, "edges": n_edges / Q},
+        "store": stats, "ingest_s": ingest_s, "commit_s": commit_s,
+    }
+    if args.cpu_seconds > 0 and wl.num_instances == 1:
+        result["cpu_baseline"] = cpu_baseline(wl, policy, wl.seed, args.cpu_seconds, out, torch)
+    else:
+        result["cpu_baseline"] = None
+    plan.close()
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -60,8 +60,8 @@ struct DeviceArray {
 struct tns_plan {
     tns_config cfg;
     std::unique_ptr<tns::Store> store;
-    DeviceArray<tns::NodeRec> d_nodes;
-    DeviceArray<tns::BlockRec> d_blocks;
+    DeviceArray<tns::NodeLine> d_nodes;
+    DeviceArray<tns::BlockRec> d_dir;
     DeviceArray<tns::Edge> d_edges;
     bool committed = false;
 };
@@ -156,15 +156,15 @@ int tns_commit(tns_plan* plan, void* hip_stream) {
     int rc;
     // at least one element each, so that the kernels always get valid base pointers
     if ((rc = ensure_capacity(plan->d_nodes, std::max<int64_t>(s.nodes.size(), 1), s.nodes, "allocating node table"))) return rc;
-    if ((rc = ensure_capacity(plan->d_blocks, std::max<int64_t>(s.blocks.size(), 1), s.blocks, "allocating block records"))) return rc;
+    if ((rc = ensure_capacity(plan->d_dir, std::max<int64_t>(s.dir.size(), 1), s.dir, "allocating the block directory"))) return rc;
     if ((rc = ensure_capacity(plan->d_edges, std::max<int64_t>(s.edges.size(), 1), s.edges, "allocating edge data"))) return rc;
     if ((rc = upload_dirty(plan->d_nodes, s.nodes, stream, "uploading node table"))) return rc;
-    if ((rc = upload_dirty(plan->d_blocks, s.blocks, stream, "uploading block records"))) return rc;
+    if ((rc = upload_dirty(plan->d_dir, s.dir, stream, "uploading the block directory"))) return rc;
     if ((rc = upload_dirty(plan->d_edges, s.edges, stream, "uploading edge data"))) return rc;
     const hipError_t e = hipStreamSynchronize(stream);
     if (e != hipSuccess) return fail_hip(e, "waiting for the upload");
     s.nodes.clear_dirty();
-    s.blocks.clear_dirty();
+    s.dir.clear_dirty();
     s.edges.clear_dirty();
     plan->committed = true;
     return TNS_OK;
@@ -198,7 +198,7 @@ static int fill_sample_args(tns_plan* plan, int64_t Q, const int32_t* d_targets,
     if (Q > (int64_t(1) << 36)) return fail(TNS_ESIZE, "more than 2^36 queries in one call: split the batch");
     a = tns::SampleArgs{};
     a.nodes = plan->d_nodes.ptr;
-    a.blocks = plan->d_blocks.ptr;
+    a.dir = plan->d_dir.ptr;
     a.edges = plan->d_edges.ptr;
     a.targets = d_targets;
     a.t_start = d_t_start;
@@ -206,7 +206,7 @@ static int fill_sample_args(tns_plan* plan, int64_t Q, const int32_t* d_targets,
     a.inst_rowptr = plan->cfg.num_instances == 1 ? nullptr : d_inst_rowptr;
     a.Q = Q;
     a.num_nodes = plan->cfg.num_nodes;
-    a.num_blocks = plan->d_blocks.used;
+    a.num_dir = plan->d_dir.used;
     a.qid_base = query_id_base;
     a.seed = plan->cfg.seed;
     a.num_instances = plan->cfg.num_instances;
@@ -322,7 +322,8 @@ int tns_stats(const tns_plan* plan, int32_t instance, tns_stats_t* out) {
     }
     const int64_t n_nodes = (int64_t)(i1 - i0) * s.config().num_nodes;
     r.avg_list_len = n_nodes ? (double)r.num_blocks / (double)n_nodes : 0.0;
-    r.metadata_bytes = n_nodes * (int64_t)sizeof(tns::NodeRec) + r.num_blocks * (int64_t)sizeof(tns::BlockRec);
+    // node lines of the instance(s) plus the directory pool (shared by all instances, counted in full)
+    r.metadata_bytes = n_nodes * (int64_t)sizeof(tns::NodeLine) + s.dir.size() * (int64_t)sizeof(tns::BlockRec);
     *out = r;
     return TNS_OK;
 }
@@ -335,14 +336,13 @@ int64_t tns_node_blocks(const tns_plan* plan, int32_t instance, int32_t node, in
     if (instance < 0 || instance >= s.config().num_instances || node < 0 || node >= s.config().num_nodes)
         return fail(TNS_ERANGE, "instance or node out of range");
     const int64_t nidx = s.node_index(instance, node);
-    int64_t n = 0;
-    for (int32_t b = s.head_of(nidx); b >= 0; b = s.blocks[b].next, ++n) {
-        if (n >= max_blocks) continue;
-        const tns::BlockRec& r = s.blocks[b];
-        if (cap) cap[n] = r.cap;
-        if (size) size[n] = r.size;
-        if (t_min) t_min[n] = r.t_min;
-        if (t_max) t_max[n] = r.t_max;
+    const int64_t n = s.nodes[nidx].nblocks;
+    for (int64_t i = 0; i < n && i < max_blocks; ++i) {
+        const tns::BlockRec& r = s.block_of(nidx, (int32_t)i);
+        if (cap) cap[i] = s.block_cap(nidx, (int32_t)i);
+        if (size) size[i] = tns::rec_size(r);
+        if (t_min) t_min[i] = r.t_min;
+        if (t_max) t_max[i] = r.t_max;
     }
     return n;
 }
@@ -350,10 +350,10 @@ int64_t tns_node_blocks(const tns_plan* plan, int32_t instance, int32_t node, in
 int tns_destroy(tns_plan* plan) {
     g_err.clear();
     if (!plan) return TNS_OK;
-    if (plan->d_nodes.ptr || plan->d_blocks.ptr || plan->d_edges.ptr) {
+    if (plan->d_nodes.ptr || plan->d_dir.ptr || plan->d_edges.ptr) {
         DeviceGuard guard(plan->cfg.device);
         if (plan->d_nodes.ptr) (void)hipFree(plan->d_nodes.ptr);
-        if (plan->d_blocks.ptr) (void)hipFree(plan->d_blocks.ptr);
+        if (plan->d_dir.ptr) (void)hipFree(plan->d_dir.ptr);
         if (plan->d_edges.ptr) (void)hipFree(plan->d_edges.ptr);
     }
     delete plan;

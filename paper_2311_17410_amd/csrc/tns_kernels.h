@@ -11,8 +11,8 @@ namespace tns {
 
 struct SampleArgs {
     // store (device)
-    const NodeRec* nodes;
-    const BlockRec* blocks;
+    const NodeLine* nodes;
+    const BlockRec* dir;     // directory pool: record runs of nodes with more than kInlineBlocks blocks
     const Edge* edges;
     // queries (device)
     const int32_t* targets;
@@ -29,7 +29,7 @@ struct SampleArgs {
     unsigned long long* counters;
     int64_t Q;
     int64_t num_nodes;
-    int64_t num_blocks;  // block records on the device (walks never index past it)
+    int64_t num_dir;     // records in the directory pool (walks never index past it)
     int64_t qid_base;
     uint64_t seed;
     int32_t num_instances;

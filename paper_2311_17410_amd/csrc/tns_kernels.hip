@@ -43,36 +43,96 @@ __device__ __forceinline__ uint64_t pick_rank(uint64_t seed, int64_t qid, int32_
     return ((z >> 32) * c) >> 32;
 }
 
-// first index i in [0, n) with ts[i] >= x (STRICT=false) or ts[i] > x (STRICT=true)
-template <bool STRICT>
-__device__ __forceinline__ int32_t first_not_before(const Edge* __restrict__ e, int32_t n, float x, int32_t& probes) {
-    int32_t lo = 0, hi = n;
-    while (lo < hi) {
-        const int32_t mid = lo + ((hi - lo) >> 1);
-        const float t = e[mid].ts;
-        ++probes;
-        const bool ge = STRICT ? (t > x) : (t >= x);
-        if (ge) hi = mid; else lo = mid + 1;
-    }
-    return lo;
-}
+// State of one lane's walk over the blocks of its target node, newest block first
+// (Algorithm 1).  `t` numbers the blocks in visiting order.
+template <int POLICY, bool INCL, typename pos_t>
+struct Walk {
+    float tb, te;                 // window [tb, te) or [tb, te]
+    int32_t f;
+    pos_t* s_pos;                 // this lane's f slots in LDS: positions of the selected edges
+    const Edge* __restrict__ edges;
+    int32_t k = 0;                // slots filled so far (newest candidates first)
+    int64_t c = 0;                // uniform: candidates seen in all overlapping blocks
+    int32_t t_first = -1, t_last = -1, hi_first = 0, lo_last = 0;   // uniform: first/last overlapping block
+    int32_t n_blocks = 0, n_probes = 0;                              // counted for the byte model
 
-struct Window {
-    int32_t lo, hi;
+    // first index i in [0, n) with ts[i] >= x (STRICT=false) or ts[i] > x (STRICT=true)
+    template <bool STRICT>
+    __device__ __forceinline__ int32_t first_not_before(const Edge* __restrict__ e, int32_t n, float x) {
+        int32_t lo = 0, hi = n;
+        while (lo < hi) {
+            const int32_t mid = lo + ((hi - lo) >> 1);
+            const float t = e[mid].ts;
+            ++n_probes;
+            const bool ge = STRICT ? (t > x) : (t >= x);
+            if (ge) hi = mid; else lo = mid + 1;
+        }
+        return lo;
+    }
+
+    // Examine one block; returns false when no older block can contribute.
+    __device__ __forceinline__ bool step(const BlockRec& r, int32_t t) {
+        ++n_blocks;
+        if (INCL ? (te < r.t_min) : (te <= r.t_min)) return true;   // block lies after the window: next older
+        if (tb > r.t_max) return false;                             // block lies before the window: stop
+        const int32_t size = rec_size(r);
+        const int64_t off = rec_off(r);
+        // candidate range [lo, hi) of the block; t_min / t_max settle most cases without a search
+        int32_t hi = size;
+        const bool all_before_end = INCL ? (te >= r.t_max) : (te > r.t_max);
+        if (!all_before_end) hi = first_not_before<INCL>(edges + off, size, te);
+        int32_t lo = 0;
+        if (tb > r.t_min) lo = first_not_before<false>(edges + off, hi, tb);
+        const int32_t cnt = hi - lo;
+        if (cnt > 0) {
+            const int32_t take = min(f - k, cnt);
+            for (int32_t j = 0; j < take; ++j) s_pos[k + j] = (pos_t)(off + hi - 1 - j);
+            k += take > 0 ? take : 0;
+            if (POLICY == 1) {
+                if (t_first < 0) { t_first = t; hi_first = hi; }
+                t_last = t; lo_last = lo;
+                c += cnt;
+            }
+        }
+        if (lo > 0) return false;                  // everything older is before the window
+        if (POLICY == 0 && k >= f) return false;   // recent: the newest f are found
+        return true;
+    }
+
+    // Uniform with more candidates than slots: f independent picks, rank counted from the
+    // oldest candidate, stored as the negated distance from the newest one until resolved.
+    __device__ __forceinline__ void draw(uint64_t seed, int64_t qid) {
+        for (int32_t j = 0; j < f; ++j) {
+            const int64_t from_newest = c - 1 - (int64_t)pick_rank(seed, qid, f, j, (uint64_t)c);
+            s_pos[j] = (pos_t)(-(from_newest + 1));
+        }
+    }
+
+    // Second visit of an overlapping block: turn the ranks that fall into it into positions.
+    __device__ __forceinline__ void resolve(const BlockRec& r, int32_t t, int64_t& cum) {
+        ++n_blocks;
+        const int32_t hi = (t == t_first) ? hi_first : rec_size(r);
+        const int32_t lo = (t == t_last) ? lo_last : 0;
+        const int64_t cnt = hi - lo;
+        const int64_t off = rec_off(r);
+        for (int32_t j = 0; j < f; ++j) {
+            const int64_t sv = (int64_t)s_pos[j];
+            if (sv < 0) {
+                const int64_t rr = -(sv + 1) - cum;
+                if (rr < cnt) s_pos[j] = (pos_t)(off + hi - 1 - rr);
+            }
+        }
+        cum += cnt;
+    }
 };
 
-// Candidate range [lo, hi) of one block for the window [tb, te) or [tb, te] (INCL).  The
-// block's t_min / t_max answer most cases without touching the edge data.
-template <bool INCL>
-__device__ __forceinline__ Window block_window(const BlockRec& r, const Edge* __restrict__ edges, float tb, float te,
-                                               int32_t& probes) {
-    Window w;
-    w.hi = r.size;
-    const bool all_before_end = INCL ? (te >= r.t_max) : (te > r.t_max);
-    if (!all_before_end) w.hi = first_not_before<INCL>(edges + r.off, r.size, te, probes);
-    w.lo = 0;
-    if (tb > r.t_min) w.lo = first_not_before<false>(edges + r.off, w.hi, tb, probes);
-    return w;
+__device__ __forceinline__ BlockRec as_rec(const uint4& u) {
+    BlockRec r;
+    r.t_min = __uint_as_float(u.x);
+    r.t_max = __uint_as_float(u.y);
+    r.off_lo = u.z;
+    r.size_hi = u.w;
+    return r;
 }
 
 template <int POLICY, bool INCL, typename pos_t, bool COUNT>
@@ -82,21 +142,23 @@ __global__ void __launch_bounds__(256) tns_sample_kernel(const SampleArgs p, con
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
     const int waves_per_wg = blockDim.x >> 6;
-    pos_t* __restrict__ s_pos = reinterpret_cast<pos_t*>(smem) + (size_t)wave * kWave * stride + (size_t)lane * stride;
 
     const int64_t tile = p.xcd_remap ? xcd_tile(blockIdx.x, gridDim.x) : (int64_t)blockIdx.x;
     const int64_t q0 = (tile * waves_per_wg + wave) * kWave;
     const int64_t q = q0 + lane;
     const int32_t f = p.fanout;
 
-    int32_t k = 0;
-    int32_t n_nodes = 0, n_blocks = 0, n_probes = 0;   // traffic model counters (COUNT only)
+    Walk<POLICY, INCL, pos_t> w;
+    w.f = f;
+    w.s_pos = reinterpret_cast<pos_t*>(smem) + (size_t)wave * kWave * stride + (size_t)lane * stride;
+    w.edges = p.edges;
+    int32_t n_nodes = 0;
     if (q < p.Q) {
         const int32_t v = p.targets[q];
-        const float te = p.t_end[q];
-        const float tb = p.t_start ? p.t_start[q] : -INFINITY;
+        w.te = p.t_end[q];
+        w.tb = p.t_start ? p.t_start[q] : -INFINITY;
         int64_t nbase = 0;
-        bool ok = (uint32_t)v < (uint64_t)p.num_nodes && !(te != te) && !(tb != tb);
+        bool ok = (uint32_t)v < (uint64_t)p.num_nodes && !(w.te != w.te) && !(w.tb != w.tb);
         if (p.inst_rowptr) {
             // instance b owns queries inst_rowptr[b] .. inst_rowptr[b+1]-1
             int32_t lo = 0, hi = p.num_instances;
@@ -108,81 +170,57 @@ __global__ void __launch_bounds__(256) tns_sample_kernel(const SampleArgs p, con
             nbase = (int64_t)lo * p.num_nodes;
         }
         if (ok) {
-            const NodeRec nd = p.nodes[nbase + v];
+            // the node's 128-byte line: header + the records of up to 7 blocks, newest first
+            const uint4* __restrict__ line = reinterpret_cast<const uint4*>(p.nodes + (nbase + v));
+            const uint4 h = line[0];
             ++n_nodes;
-            int32_t b = (nd.flags & 1) ? -1 : nd.tail;
-            if (POLICY == 0) {
-                for (int32_t it = 0; it < nd.nblocks && b >= 0 && (int64_t)b < p.num_blocks && k < f; ++it) {
-                    const BlockRec r = p.blocks[b];
-                    ++n_blocks;
-                    if (INCL ? (te < r.t_min) : (te <= r.t_min)) { b = r.prev; continue; }   // block is after the window
-                    if (tb > r.t_max) break;                                                 // block is before the window
-                    const Window w = block_window<INCL>(r, p.edges, tb, te, n_probes);
-                    const int32_t take = min(f - k, w.hi - w.lo);
-                    for (int32_t j = 0; j < take; ++j) s_pos[k + j] = (pos_t)(r.off + w.hi - 1 - j);
-                    k += take > 0 ? take : 0;
-                    if (w.lo > 0) break;          // everything older is before the window
-                    b = r.prev;
-                }
-            } else {
-                // pass 1: all overlapping blocks; total candidates c; the newest f positions are
-                // recorded on the way (they are the answer when c <= f)
-                int64_t c = 0;
-                int32_t b_first = -1, hi_first = 0, b_last = -1, lo_last = 0;
-                for (int32_t it = 0; it < nd.nblocks && b >= 0 && (int64_t)b < p.num_blocks; ++it) {
-                    const BlockRec r = p.blocks[b];
-                    ++n_blocks;
-                    if (INCL ? (te < r.t_min) : (te <= r.t_min)) { b = r.prev; continue; }
-                    if (tb > r.t_max) break;
-                    const Window w = block_window<INCL>(r, p.edges, tb, te, n_probes);
-                    const int32_t cnt = w.hi - w.lo;
-                    if (cnt > 0) {
-                        if (b_first < 0) { b_first = b; hi_first = w.hi; }
-                        b_last = b; lo_last = w.lo;
-                        const int32_t take = min(f - k, cnt);
-                        for (int32_t j = 0; j < take; ++j) s_pos[k + j] = (pos_t)(r.off + w.hi - 1 - j);
-                        k += take > 0 ? take : 0;
-                        c += cnt;
-                    }
-                    if (w.lo > 0) break;
-                    b = r.prev;
-                }
-                if (c > (int64_t)f) {
-                    // f independent picks; rank counted from the oldest candidate, turned into a
-                    // distance from the newest one; unresolved entries are stored negative
-                    const int64_t qid = p.qid_base + q;
-                    for (int32_t j = 0; j < f; ++j) {
-                        const int64_t from_newest = c - 1 - (int64_t)pick_rank(p.seed, qid, f, j, (uint64_t)c);
-                        s_pos[j] = (pos_t)(-(from_newest + 1));
-                    }
-                    // pass 2: walk the overlapping blocks again and resolve rank -> position
+            const int32_t nb = (h.w & 1) ? 0 : (int32_t)h.x;      // deleted node: no blocks
+            if (nb > 0 && nb <= kInlineBlocks) {
+                uint4 L[kInlineBlocks];
+#pragma unroll
+                for (int j = 0; j < kInlineBlocks; ++j) L[j] = line[1 + j];
+                bool go = true;
+#pragma unroll
+                for (int j = 0; j < kInlineBlocks; ++j)
+                    if (go && j < nb) go = w.step(as_rec(L[j]), j);
+                if (POLICY == 1 && w.c > (int64_t)f) {
+                    w.draw(p.seed, p.qid_base + q);
                     int64_t cum = 0;
-                    b = b_first;
-                    for (int32_t it = 0; it < nd.nblocks && b >= 0 && (int64_t)b < p.num_blocks; ++it) {
-                        const BlockRec r = p.blocks[b];
-                    ++n_blocks;
-                        const int32_t hi = (b == b_first) ? hi_first : r.size;
-                        const int32_t lo = (b == b_last) ? lo_last : 0;
-                        const int64_t cnt = hi - lo;
-                        for (int32_t j = 0; j < f; ++j) {
-                            const int64_t sv = (int64_t)s_pos[j];
-                            if (sv < 0) {
-                                const int64_t rr = -(sv + 1) - cum;
-                                if (rr < cnt) s_pos[j] = (pos_t)(r.off + hi - 1 - rr);
-                            }
-                        }
-                        cum += cnt;
-                        if (b == b_last) break;
-                        b = r.prev;
+#pragma unroll
+                    for (int j = 0; j < kInlineBlocks; ++j)
+                        if (j >= w.t_first && j <= w.t_last) w.resolve(as_rec(L[j]), j, cum);
+                }
+            } else if (nb > kInlineBlocks) {
+                // long list: all records of the node, oldest first, in one run of the directory
+                const int64_t d0 = (int64_t)h.z * kDirAlign;
+                if (d0 + nb <= p.num_dir) {
+                    const BlockRec* __restrict__ d = p.dir + d0;
+                    // newest block that starts before the window end (binary search instead of
+                    // stepping through the newer blocks one by one)
+                    int32_t lo = 0, hi = nb;
+                    while (lo < hi) {
+                        const int32_t mid = lo + ((hi - lo) >> 1);
+                        const float tm = d[mid].t_min;
+                        ++w.n_blocks;
+                        if (INCL ? (tm > w.te) : (tm >= w.te)) hi = mid; else lo = mid + 1;
+                    }
+                    const int32_t j0 = lo - 1;
+                    bool go = true;
+                    for (int32_t j = j0; j >= 0 && go; --j) go = w.step(d[j], j0 - j);
+                    if (POLICY == 1 && w.c > (int64_t)f) {
+                        w.draw(p.seed, p.qid_base + q);
+                        int64_t cum = 0;
+                        for (int32_t t = w.t_first; t <= w.t_last; ++t) w.resolve(d[j0 - t], t, cum);
                     }
                 }
             }
         }
     }
+    const int32_t k = w.k;
     if (COUNT) {
         // totals of what this launch reads: node entries, block records, timestamp probes, edges
-        unsigned long long v4[4] = {(unsigned long long)n_nodes, (unsigned long long)n_blocks,
-                                    (unsigned long long)n_probes, (unsigned long long)k};
+        unsigned long long v4[4] = {(unsigned long long)n_nodes, (unsigned long long)w.n_blocks,
+                                    (unsigned long long)w.n_probes, (unsigned long long)k};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             unsigned long long v = v4[i];

@@ -1,35 +1,67 @@
 // Record layouts shared by the host-side store builder and the device kernels.
 //
 // The paper (section 4.1) lists what a node entry and an edge block hold but not their byte
-// layout ("lightweight structures (72 bytes)"), so the layout here is chosen for 64-byte HBM
-// sectors: a node entry is 16 bytes, a block record 32 bytes (two per sector, never
-// straddling one), an edge 12 bytes with timestamp, neighbour and edge id side by side so that
-// the timestamps probed by the in-block search and the ids gathered afterwards share sectors.
-// Pointers are 32-bit block indices and 64-bit edge offsets into flat device arrays.
+// layout ("lightweight structures (72 bytes)") and links a node's blocks into a doubly-linked
+// list.  On MI355X every dependent random read costs a 128-byte line from HBM, so a linked
+// list of separately allocated records costs one line per block visited.  Here the records of
+// one node sit next to each other instead:
+//
+//   * NodeLine (128 bytes, line-aligned): the node entry (list length, degree, validity) plus
+//     the records of up to 7 blocks, newest first.  One line read gives Algorithm 1 everything
+//     it needs to skip, stop or search for nodes with short lists.
+//   * nodes with longer lists keep all their records, oldest first, in one contiguous run of
+//     the directory pool; the walk starts with a binary search over it instead of stepping
+//     through the newer blocks one by one.
+//   * BlockRec (16 bytes): earliest and latest timestamp, number of edges, offset of the
+//     block's edges.  The capacity is not needed by sampling: every block but the newest is
+//     full, and the newest block's capacity is kept on the host.
+//   * Edge (12 bytes): timestamp, neighbour id, edge id side by side, so the timestamps probed
+//     by the in-block search and the ids gathered afterwards share lines.
 #pragma once
 #include <cstdint>
 
 namespace tns {
 
-// Node table entry (section 4.1: last block of the list, list length, degree, validity).
-// The first block is reachable through the prev links and is kept on the host side only.
-struct NodeRec {
-    int32_t tail;     // index of the newest block, -1 if the node has no edge
-    int32_t nblocks;  // list length
-    int32_t degree;   // stored edges (out-degree)
-    int32_t flags;    // bit 0: node deleted
-};
-static_assert(sizeof(NodeRec) == 16, "node entry is 16 bytes");
+constexpr int kInlineBlocks = 7;
+constexpr int64_t kMaxBlockEdges = (int64_t(1) << 24) - 1;  // size field is 24 bits
+constexpr int64_t kMaxEdgeOffset = (int64_t(1) << 40) - 1;  // offset field is 40 bits
 
-// Edge block metadata (section 4.1: capacity, fill, where the edge data is, earliest and
-// latest timestamp; prev/next links of the chronological doubly-linked list).
+// Edge block metadata (section 4.1: fill, where the edge data is, earliest and latest time).
 struct BlockRec {
     float t_min, t_max;  // earliest / latest edge time in the block
-    int32_t size, cap;   // edges held / block size
-    int64_t off;         // offset of the block's first edge in the edge array
-    int32_t prev, next;  // older / newer block of the same node, -1 at the ends
+    uint32_t off_lo;     // low 32 bits of the offset of the block's first edge in the edge array
+    uint32_t size_hi;    // bits 0-23: edges held; bits 24-31: offset bits 32-39
 };
-static_assert(sizeof(BlockRec) == 32, "block record is 32 bytes");
+static_assert(sizeof(BlockRec) == 16, "block record is 16 bytes");
+
+#if defined(__HIPCC__)
+#define TNS_HD __host__ __device__ inline __attribute__((always_inline))
+#else
+#define TNS_HD inline
+#endif
+TNS_HD int32_t rec_size(const BlockRec& r) { return (int32_t)(r.size_hi & 0xffffffu); }
+TNS_HD int64_t rec_off(const BlockRec& r) { return (int64_t)r.off_lo | ((int64_t)(r.size_hi >> 24) << 32); }
+TNS_HD BlockRec make_rec(float t_min, float t_max, int64_t off, int32_t size) {
+    BlockRec r;
+    r.t_min = t_min;
+    r.t_max = t_max;
+    r.off_lo = (uint32_t)(off & 0xffffffffu);
+    r.size_hi = ((uint32_t)size & 0xffffffu) | ((uint32_t)(off >> 32) << 24);
+    return r;
+}
+
+// Node table entry (section 4.1: list length, degree, validity, access to the blocks).
+struct alignas(128) NodeLine {
+    int32_t nblocks;   // list length
+    int32_t degree;    // stored edges (out-degree)
+    uint32_t dir_line; // nblocks > kInlineBlocks: where the node's records start in the directory
+                       // pool, in units of kDirAlign records (oldest record first)
+    int32_t flags;     // bit 0: node deleted
+    BlockRec rec[kInlineBlocks];  // nblocks <= kInlineBlocks: rec[0] newest ... rec[nblocks-1] oldest
+};
+static_assert(sizeof(NodeLine) == 128, "node entry is one 128-byte line");
+
+constexpr int kDirAlign = 8;  // directory runs start on a 128-byte line
 
 // One entry of the graph edge data.  Inside a block, entries are in (timestamp, arrival) order.
 struct Edge {

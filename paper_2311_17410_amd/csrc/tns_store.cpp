@@ -12,11 +12,56 @@ namespace tns {
 Store::Store(const StoreConfig& cfg) : cfg_(cfg), totals_((size_t)cfg.num_instances) {
     const int64_t total_nodes = (int64_t)cfg.num_instances * cfg.num_nodes;
     if (total_nodes > 0) {
-        nodes.grow(total_nodes);
-        for (int64_t i = 0; i < total_nodes; ++i) nodes.raw(i).tail = -1;
+        nodes.grow(total_nodes);   // zero-filled: no blocks, degree 0, valid
         nodes.mark_all();
     }
-    head_.assign((size_t)total_nodes, -1);
+    tail_cap_.assign((size_t)total_nodes, 0);
+    dir_cap_.assign((size_t)total_nodes, 0);
+}
+
+const BlockRec& Store::block_of(int64_t nidx, int32_t i) const {
+    const NodeLine& nd = nodes[nidx];
+    if (nd.nblocks <= kInlineBlocks) return nd.rec[nd.nblocks - 1 - i];
+    return dir[(int64_t)nd.dir_line * kDirAlign + i];
+}
+
+int32_t Store::block_cap(int64_t nidx, int32_t i) const {
+    const NodeLine& nd = nodes[nidx];
+    // only the newest block can have room
+    return i == nd.nblocks - 1 ? tail_cap_[(size_t)nidx] : rec_size(block_of(nidx, i));
+}
+
+BlockRec& Store::tail_rec(NodeLine& nd) {
+    if (nd.nblocks <= kInlineBlocks) return nd.rec[0];
+    const int64_t i = (int64_t)nd.dir_line * kDirAlign + nd.nblocks - 1;
+    return dir.mut(i);
+}
+
+// Link a new (newest) block to the node: O(1) inline shift, or an append to the node's run in
+// the directory pool (runs grow by doubling into a fresh place; the old run is abandoned).
+void Store::append_block(int64_t nidx, NodeLine& nd, const BlockRec& r, int32_t cap) {
+    if (nd.nblocks < kInlineBlocks) {
+        for (int j = nd.nblocks; j > 0; --j) nd.rec[j] = nd.rec[j - 1];
+        nd.rec[0] = r;
+    } else {
+        int32_t& dcap = dir_cap_[(size_t)nidx];
+        if (nd.nblocks == dcap || dcap == 0) {
+            const int32_t ncap = dcap ? dcap * 2 : 2 * kDirAlign;
+            const int64_t start = dir.grow(ncap);
+            if (dcap == 0) {
+                for (int j = 0; j < kInlineBlocks; ++j) dir.raw(start + j) = nd.rec[kInlineBlocks - 1 - j];
+            } else {
+                const int64_t old = (int64_t)nd.dir_line * kDirAlign;
+                for (int32_t j = 0; j < nd.nblocks; ++j) dir.raw(start + j) = dir[old + j];
+            }
+            dir.mark(start, nd.nblocks);
+            nd.dir_line = (uint32_t)(start / kDirAlign);
+            dcap = ncap;
+        }
+        dir.mut((int64_t)nd.dir_line * kDirAlign + nd.nblocks) = r;
+    }
+    nd.nblocks += 1;
+    tail_cap_[(size_t)nidx] = cap;
 }
 
 namespace {
@@ -92,8 +137,9 @@ int Store::add_edges(int32_t inst, const int32_t* src, const int32_t* dst, const
             }
             if (!sorted)
                 std::stable_sort(ord + g0, ord + g1, [ts](uint32_t a, uint32_t b) { return ts[a] < ts[b]; });
-            const NodeRec& nd = nodes[node_index(inst, v)];
-            if (nd.tail >= 0 && ts[ord[g0]] < blocks[nd.tail].t_max) {
+            const int64_t nidx = node_index(inst, v);
+            const NodeLine& nd = nodes[nidx];
+            if (nd.nblocks > 0 && ts[ord[g0]] < block_of(nidx, nd.nblocks - 1).t_max) {
                 err = "node " + std::to_string(v) + " would receive an edge older than its newest stored edge";
                 return TNS_EORDER;
             }
@@ -101,9 +147,14 @@ int Store::add_edges(int32_t inst, const int32_t* src, const int32_t* dst, const
         }
     }
 
-    // Capacity checks before anything is changed.
-    if (blocks.size() + m >= (int64_t)INT32_MAX) {
-        err = "more than 2^31-1 blocks";
+    // Limit of the record encoding, checked before anything is changed.  Worst case: every edge
+    // of the batch opens a block, of at most max(batch share, min(degree, tau)) slots.
+    int64_t stored = 0;
+    for (const InstanceTotals& t : totals_) stored += t.edges;
+    const int64_t by_tau = m * std::max<int64_t>(1, cfg_.tau);   // m, tau < 2^31: no overflow
+    const int64_t worst_new_slots = m + (cfg_.sizing == TNS_SIZING_FIXED ? by_tau : std::min(by_tau, stored + m));
+    if (edges.size() + worst_new_slots > kMaxEdgeOffset) {
+        err = "edge array would exceed 2^40 slots";
         return TNS_ESIZE;
     }
 
@@ -114,7 +165,7 @@ int Store::add_edges(int32_t inst, const int32_t* src, const int32_t* dst, const
         int64_t g1 = g0 + 1;
         while (g1 < m && src[ord[g1]] == v) ++g1;
         const int64_t nidx = node_index(inst, v);
-        NodeRec& nd = nodes.mut(nidx);
+        NodeLine& nd = nodes.mut(nidx);
         int64_t i = g0;
         auto put = [&](int64_t pos, uint32_t e) {
             Edge& ed = edges.raw(pos);
@@ -122,15 +173,15 @@ int Store::add_edges(int32_t inst, const int32_t* src, const int32_t* dst, const
             ed.nbr = dst[e];
             ed.eid = eid ? eid[e] : (int32_t)(eid_base + (int64_t)e);
         };
-        if (nd.tail >= 0) {
-            BlockRec& tb = blocks.raw(nd.tail);
-            int64_t take = std::min<int64_t>(tb.cap - tb.size, g1 - i);
+        if (nd.nblocks > 0) {
+            BlockRec& tb = tail_rec(nd);
+            const int32_t size = rec_size(tb);
+            const int64_t off = rec_off(tb);
+            const int64_t take = std::min<int64_t>(tail_cap_[(size_t)nidx] - size, g1 - i);
             if (take > 0) {
-                for (int64_t k = 0; k < take; ++k) put(tb.off + tb.size + k, ord[i + k]);
-                edges.mark(tb.off + tb.size, take);
-                tb.size += (int32_t)take;
-                tb.t_max = ts[ord[i + take - 1]];
-                blocks.mark(nd.tail, 1);
+                for (int64_t k = 0; k < take; ++k) put(off + size + k, ord[i + k]);
+                edges.mark(off + size, take);
+                tb = make_rec(tb.t_min, ts[ord[i + take - 1]], off, size + (int32_t)take);
                 nd.degree += (int32_t)take;
                 i += take;
             }
@@ -141,23 +192,12 @@ int Store::add_edges(int32_t inst, const int32_t* src, const int32_t* dst, const
             if (cfg_.sizing == TNS_SIZING_STRAWMAN) cap = rest;
             else if (cfg_.sizing == TNS_SIZING_FIXED) cap = cfg_.tau;
             else cap = std::max<int64_t>(rest, std::min<int64_t>(nd.degree, cfg_.tau));  // b_v = min(deg(v), tau)
+            cap = std::min(cap, kMaxBlockEdges);   // limit of the record's size field
             const int64_t take = std::min(rest, cap);
-            const int64_t bi = blocks.grow(1);
             const int64_t off = edges.grow(cap);
             for (int64_t k = 0; k < take; ++k) put(off + k, ord[i + k]);
             edges.mark(off, cap);
-            BlockRec& nb = blocks.mut(bi);
-            nb.t_min = ts[ord[i]];
-            nb.t_max = ts[ord[i + take - 1]];
-            nb.size = (int32_t)take;
-            nb.cap = (int32_t)cap;
-            nb.off = off;
-            nb.prev = nd.tail;
-            nb.next = -1;
-            if (nd.tail >= 0) blocks.mut(nd.tail).next = (int32_t)bi;
-            else head_[(size_t)nidx] = (int32_t)bi;
-            nd.tail = (int32_t)bi;
-            nd.nblocks += 1;
+            append_block(nidx, nd, make_rec(ts[ord[i]], ts[ord[i + take - 1]], off, (int32_t)take), (int32_t)cap);
             nd.degree += (int32_t)take;
             tot.slots += cap;
             tot.blocks += 1;

@@ -47,8 +47,10 @@ public:
         int64_t start = n_;
         int64_t need_pages = (n_ + count + kPage - 1) >> PAGE_LOG2;
         while ((int64_t)pages_.size() < need_pages) {
-            T* p = static_cast<T*>(std::calloc((size_t)kPage, sizeof(T)));
+            // 128-byte aligned (records are line-sized) and zero-filled
+            T* p = static_cast<T*>(std::aligned_alloc(128, (size_t)kPage * sizeof(T)));
             if (!p) throw std::bad_alloc();
+            std::memset(static_cast<void*>(p), 0, (size_t)kPage * sizeof(T));
             pages_.push_back(p);
         }
         n_ += count;
@@ -106,16 +108,22 @@ public:
     const StoreConfig& config() const { return cfg_; }
     const InstanceTotals& totals(int32_t inst) const { return totals_[inst]; }
     int64_t node_index(int32_t inst, int64_t v) const { return (int64_t)inst * cfg_.num_nodes + v; }
-    int32_t head_of(int64_t nidx) const { return head_[nidx]; }
+    // i-th block of a node in chronological order (0 = oldest) and its capacity
+    const BlockRec& block_of(int64_t nidx, int32_t i) const;
+    int32_t block_cap(int64_t nidx, int32_t i) const;
 
-    Paged<NodeRec> nodes;
-    Paged<BlockRec> blocks;
+    Paged<NodeLine, 18, 9> nodes;   // 128-byte entries: 2^18 per page, change tracking per 64 KiB
+    Paged<BlockRec> dir;            // directory pool: record runs of nodes with long lists
     Paged<Edge> edges;
 
 private:
+    BlockRec& tail_rec(NodeLine& nd);
+    void append_block(int64_t nidx, NodeLine& nd, const BlockRec& r, int32_t cap);
+
     StoreConfig cfg_;
     std::vector<InstanceTotals> totals_;
-    std::vector<int32_t> head_;           // oldest block per node (host side only)
+    std::vector<int32_t> tail_cap_;       // capacity of each node's newest block (host side only)
+    std::vector<int32_t> dir_cap_;        // records reserved for the node in the directory pool (0: inline)
     std::vector<uint32_t> ord_, tmp_;     // scratch: batch positions grouped by source node
 };
 

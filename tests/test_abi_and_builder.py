@@ -82,6 +82,10 @@ def test_sizing_closed_forms():
         B.tns_add_edges(h, 0, [0], [i], [float(i)])
     caps = list(B.tns_node_blocks(h, 0, 0)["cap"])
     assert caps[:6] == [1, 1, 2, 4, 8, 16] and set(caps[6:]) == {16}
+    # 11 blocks > 7 inline records: the node's records moved to a 16-record directory run
+    assert len(caps) == 11 and B.tns_stats(h)["metadata_bytes"] == 128 + 16 * 16
+    blk = B.tns_node_blocks(h, 0, 0)
+    assert list(blk["t_min"][:4]) == [0.0, 1.0, 2.0, 4.0] and blk["t_max"][-1] == 99.0
     B.tns_destroy(h)
     h = B.tns_plan_create(num_nodes=2, fanout=3, block_threshold=8)
     B.tns_add_edges(h, 0, [0] * 5, [1] * 5, np.arange(5))
@@ -91,7 +95,7 @@ def test_sizing_closed_forms():
     assert list(B.tns_node_blocks(h, 0, 0)["cap"]) == [5, 5, 28, 8]
     st = B.tns_stats(h)
     assert st["wasted_slots"] == 7 and st["num_edges"] == 39 and st["max_list_len"] == 4
-    assert st["edge_data_bytes"] == 46 * 12 and st["metadata_bytes"] == 2 * 16 + 4 * 32
+    assert st["edge_data_bytes"] == 46 * 12 and st["metadata_bytes"] == 2 * 128      # two node lines, no directory run
     B.tns_destroy(h)
 
 

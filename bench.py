@@ -158,7 +158,7 @@ def main() -> int:
     torch.cuda.synchronize()
     n_nodes, n_blocks, n_probes, n_edges = (int(x) for x in counters.cpu())
     q_in = 8 + (4 if d_tb is not None else 0) + (0 if d_rp is None else 0)
-    bytes_sample = {"queries": q_in * Q, "node_entries": 16 * n_nodes, "block_records": 32 * n_blocks,
+    bytes_sample = {"queries": q_in * Q, "node_entries": 16 * n_nodes, "block_records": 16 * n_blocks,
                     "timestamp_probes": 4 * n_probes, "edge_gather": 12 * n_edges, "padded_write": (12 * f + 4) * Q}
     alg_sample = sum(bytes_sample.values())
     alg_compact = (4 + 4 + 12 * f) * Q + 8 * (Q + 1) + 12 * n_edges     # counts twice, padded once, rowptr, dense

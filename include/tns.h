@@ -57,7 +57,10 @@ enum { TNS_SIZING_ADAPTIVE = 0, TNS_SIZING_STRAWMAN = 1, TNS_SIZING_FIXED = 2 };
 enum { TNS_MAX_FANOUT = 64 };
 /* tns_config.flags */
 enum {
-    TNS_FLAG_NO_XCD_REMAP = 1 /* keep the hardware's round-robin workgroup->XCD order (for measurements) */
+    TNS_FLAG_NO_XCD_REMAP = 1, /* keep the hardware's round-robin workgroup->XCD order (for measurements) */
+    TNS_FLAG_NO_NODE_SLAB = 2  /* do not reserve one 128-byte edge line per non-empty node for its first
+                                  blocks: less memory for graphs of mostly degree-1 nodes, more lines
+                                  read per query                                                        */
 };
 
 typedef struct {

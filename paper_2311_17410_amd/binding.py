@@ -20,6 +20,7 @@ TNS_POLICY_RECENT, TNS_POLICY_UNIFORM = 0, 1
 TNS_SIZING_ADAPTIVE, TNS_SIZING_STRAWMAN, TNS_SIZING_FIXED = 0, 1, 2
 TNS_MAX_FANOUT = 64
 TNS_FLAG_NO_XCD_REMAP = 1
+TNS_FLAG_NO_NODE_SLAB = 2
 
 EXPORTS = ["tns_plan_create", "tns_add_edges", "tns_commit", "tns_workspace", "tns_run", "tns_compact", "tns_traffic_model", "tns_stats",
            "tns_node_blocks", "tns_destroy", "tns_strerror", "tns_last_error"]

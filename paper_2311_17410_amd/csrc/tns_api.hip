@@ -62,7 +62,7 @@ struct tns_plan {
     std::unique_ptr<tns::Store> store;
     DeviceArray<tns::NodeLine> d_nodes;
     DeviceArray<tns::BlockRec> d_dir;
-    DeviceArray<tns::Edge> d_edges;
+    DeviceArray<tns::EdgeLine> d_edges;
     bool committed = false;
 };
 
@@ -124,6 +124,7 @@ int tns_plan_create(const tns_config* cfg, tns_plan** out) {
         sc.num_instances = cfg->num_instances;
         sc.tau = cfg->block_threshold;
         sc.sizing = cfg->sizing;
+        sc.node_slab = !(cfg->flags & TNS_FLAG_NO_NODE_SLAB);
         p->store.reset(new tns::Store(sc));
         *out = p.release();
     } catch (const std::bad_alloc&) {
@@ -157,15 +158,15 @@ int tns_commit(tns_plan* plan, void* hip_stream) {
     // at least one element each, so that the kernels always get valid base pointers
     if ((rc = ensure_capacity(plan->d_nodes, std::max<int64_t>(s.nodes.size(), 1), s.nodes, "allocating node table"))) return rc;
     if ((rc = ensure_capacity(plan->d_dir, std::max<int64_t>(s.dir.size(), 1), s.dir, "allocating the block directory"))) return rc;
-    if ((rc = ensure_capacity(plan->d_edges, std::max<int64_t>(s.edges.size(), 1), s.edges, "allocating edge data"))) return rc;
+    if ((rc = ensure_capacity(plan->d_edges, std::max<int64_t>(s.lines.size(), 1), s.lines, "allocating edge data"))) return rc;
     if ((rc = upload_dirty(plan->d_nodes, s.nodes, stream, "uploading node table"))) return rc;
     if ((rc = upload_dirty(plan->d_dir, s.dir, stream, "uploading the block directory"))) return rc;
-    if ((rc = upload_dirty(plan->d_edges, s.edges, stream, "uploading edge data"))) return rc;
+    if ((rc = upload_dirty(plan->d_edges, s.lines, stream, "uploading edge data"))) return rc;
     const hipError_t e = hipStreamSynchronize(stream);
     if (e != hipSuccess) return fail_hip(e, "waiting for the upload");
     s.nodes.clear_dirty();
     s.dir.clear_dirty();
-    s.edges.clear_dirty();
+    s.lines.clear_dirty();
     plan->committed = true;
     return TNS_OK;
 }
@@ -199,7 +200,7 @@ static int fill_sample_args(tns_plan* plan, int64_t Q, const int32_t* d_targets,
     a = tns::SampleArgs{};
     a.nodes = plan->d_nodes.ptr;
     a.dir = plan->d_dir.ptr;
-    a.edges = plan->d_edges.ptr;
+    a.edges = reinterpret_cast<const uint32_t*>(plan->d_edges.ptr);
     a.targets = d_targets;
     a.t_start = d_t_start;
     a.t_end = d_t_end;
@@ -214,7 +215,7 @@ static int fill_sample_args(tns_plan* plan, int64_t Q, const int32_t* d_targets,
     a.policy = plan->cfg.policy;
     a.inclusive_end = plan->cfg.inclusive_end;
     a.xcd_remap = (plan->cfg.flags & TNS_FLAG_NO_XCD_REMAP) ? 0 : 1;
-    a.wide_offsets = plan->d_edges.used >= (int64_t(1) << 31) ? 1 : 0;
+    a.wide_offsets = plan->d_edges.used * 32 >= (int64_t(1) << 31) ? 1 : 0;   // word indices beyond int32
     return TNS_OK;
 }
 
@@ -314,12 +315,14 @@ int tns_stats(const tns_plan* plan, int32_t instance, tns_stats_t* out) {
         r.num_blocks += t.blocks;
         r.num_edges += t.edges;
         r.wasted_slots += t.slots - t.edges;
-        r.edge_data_bytes += t.slots * (int64_t)sizeof(tns::Edge);
+
         for (int64_t v = 0; v < s.config().num_nodes; ++v) {
             const int64_t nb = s.nodes[s.node_index(i, v)].nblocks;
             if (nb > r.max_list_len) r.max_list_len = nb;
         }
     }
+    // edge lines are shared by all instances and counted in full (block slots + line padding + unused line ends)
+    r.edge_data_bytes = s.lines.size() * (int64_t)sizeof(tns::EdgeLine);
     const int64_t n_nodes = (int64_t)(i1 - i0) * s.config().num_nodes;
     r.avg_list_len = n_nodes ? (double)r.num_blocks / (double)n_nodes : 0.0;
     // node lines of the instance(s) plus the directory pool (shared by all instances, counted in full)

@@ -13,7 +13,7 @@ struct SampleArgs {
     // store (device)
     const NodeLine* nodes;
     const BlockRec* dir;     // directory pool: record runs of nodes with more than kInlineBlocks blocks
-    const Edge* edges;
+    const uint32_t* edges;   // edge lines viewed as 4-byte words: slot s starts at word slot_word(s)
     // queries (device)
     const int32_t* targets;
     const float* t_start;        // may be null: -inf

@@ -49,8 +49,8 @@ template <int POLICY, bool INCL, typename pos_t>
 struct Walk {
     float tb, te;                 // window [tb, te) or [tb, te]
     int32_t f;
-    pos_t* s_pos;                 // this lane's f slots in LDS: positions of the selected edges
-    const Edge* __restrict__ edges;
+    pos_t* s_pos;                 // this lane's f slots in LDS: word index of each selected edge
+    const uint32_t* __restrict__ edges;   // edge lines as 4-byte words
     int32_t k = 0;                // slots filled so far (newest candidates first)
     int64_t c = 0;                // uniform: candidates seen in all overlapping blocks
     int32_t t_first = -1, t_last = -1, hi_first = 0, lo_last = 0;   // uniform: first/last overlapping block
@@ -58,11 +58,11 @@ struct Walk {
 
     // first index i in [0, n) with ts[i] >= x (STRICT=false) or ts[i] > x (STRICT=true)
     template <bool STRICT>
-    __device__ __forceinline__ int32_t first_not_before(const Edge* __restrict__ e, int32_t n, float x) {
+    __device__ __forceinline__ int32_t first_not_before(int64_t off, int32_t n, float x) {
         int32_t lo = 0, hi = n;
         while (lo < hi) {
             const int32_t mid = lo + ((hi - lo) >> 1);
-            const float t = e[mid].ts;
+            const float t = __uint_as_float(edges[slot_word(off + mid)]);   // Edge::ts is the first word
             ++n_probes;
             const bool ge = STRICT ? (t > x) : (t >= x);
             if (ge) hi = mid; else lo = mid + 1;
@@ -80,13 +80,13 @@ struct Walk {
         // candidate range [lo, hi) of the block; t_min / t_max settle most cases without a search
         int32_t hi = size;
         const bool all_before_end = INCL ? (te >= r.t_max) : (te > r.t_max);
-        if (!all_before_end) hi = first_not_before<INCL>(edges + off, size, te);
+        if (!all_before_end) hi = first_not_before<INCL>(off, size, te);
         int32_t lo = 0;
-        if (tb > r.t_min) lo = first_not_before<false>(edges + off, hi, tb);
+        if (tb > r.t_min) lo = first_not_before<false>(off, hi, tb);
         const int32_t cnt = hi - lo;
         if (cnt > 0) {
             const int32_t take = min(f - k, cnt);
-            for (int32_t j = 0; j < take; ++j) s_pos[k + j] = (pos_t)(off + hi - 1 - j);
+            for (int32_t j = 0; j < take; ++j) s_pos[k + j] = (pos_t)slot_word(off + hi - 1 - j);
             k += take > 0 ? take : 0;
             if (POLICY == 1) {
                 if (t_first < 0) { t_first = t; hi_first = hi; }
@@ -119,7 +119,7 @@ struct Walk {
             const int64_t sv = (int64_t)s_pos[j];
             if (sv < 0) {
                 const int64_t rr = -(sv + 1) - cum;
-                if (rr < cnt) s_pos[j] = (pos_t)(off + hi - 1 - rr);
+                if (rr < cnt) s_pos[j] = (pos_t)slot_word(off + hi - 1 - rr);
             }
         }
         cum += cnt;
@@ -244,7 +244,7 @@ __global__ void __launch_bounds__(256) tns_sample_kernel(const SampleArgs p, con
             float t = 0.0f;
             if (j < kq) {
                 const int64_t pos = (int64_t)w_pos[ql * stride + j];
-                const Edge e = p.edges[pos];
+                const Edge e = *reinterpret_cast<const Edge*>(p.edges + pos);
                 nbr = e.nbr; eid = e.eid; t = e.ts;
             }
             p.out_nbr[out0 + s] = nbr;

@@ -16,7 +16,8 @@
 //     block's edges.  The capacity is not needed by sampling: every block but the newest is
 //     full, and the newest block's capacity is kept on the host.
 //   * Edge (12 bytes): timestamp, neighbour id, edge id side by side, so the timestamps probed
-//     by the in-block search and the ids gathered afterwards share lines.
+//     by the in-block search and the ids gathered afterwards share lines; ten edges per
+//     128-byte line (EdgeLine).
 #pragma once
 #include <cstdint>
 
@@ -24,12 +25,12 @@ namespace tns {
 
 constexpr int kInlineBlocks = 7;
 constexpr int64_t kMaxBlockEdges = (int64_t(1) << 24) - 1;  // size field is 24 bits
-constexpr int64_t kMaxEdgeOffset = (int64_t(1) << 40) - 1;  // offset field is 40 bits
+constexpr int64_t kMaxEdgeOffset = (int64_t(1) << 40) - 1;  // offset (slot index) field is 40 bits
 
 // Edge block metadata (section 4.1: fill, where the edge data is, earliest and latest time).
 struct BlockRec {
     float t_min, t_max;  // earliest / latest edge time in the block
-    uint32_t off_lo;     // low 32 bits of the offset of the block's first edge in the edge array
+    uint32_t off_lo;     // low 32 bits of the slot index of the block's first edge
     uint32_t size_hi;    // bits 0-23: edges held; bits 24-31: offset bits 32-39
 };
 static_assert(sizeof(BlockRec) == 16, "block record is 16 bytes");
@@ -70,5 +71,21 @@ struct Edge {
     int32_t eid;
 };
 static_assert(sizeof(Edge) == 12, "edge entry is 12 bytes");
+
+// The edge array is made of 128-byte lines of 10 edge slots (8 bytes unused per line), so that
+// a block of up to 10 slots allocated at a line start is read with one line, and blocks are
+// addressed by slot index: slot s lives in line s / 10 at position s % 10.
+constexpr int kSlotsPerLine = 10;
+struct alignas(128) EdgeLine {
+    Edge e[kSlotsPerLine];
+    uint32_t unused[2];
+};
+static_assert(sizeof(EdgeLine) == 128, "edge line is 128 bytes");
+
+// 4-byte word index of slot s inside the edge array (line * 32 + position * 3)
+TNS_HD int64_t slot_word(int64_t s) {
+    const int64_t line = s / kSlotsPerLine;
+    return line * 32 + (s - line * kSlotsPerLine) * 3;
+}
 
 }  // namespace tns

@@ -17,6 +17,52 @@ Store::Store(const StoreConfig& cfg) : cfg_(cfg), totals_((size_t)cfg.num_instan
     }
     tail_cap_.assign((size_t)total_nodes, 0);
     dir_cap_.assign((size_t)total_nodes, 0);
+    if (cfg.node_slab) {
+        slab_line_.assign((size_t)total_nodes, 0);
+        slab_used_.assign((size_t)total_nodes, 0);
+    }
+}
+
+int64_t Store::place_block(int64_t nidx, int64_t cap) {
+    if (cap >= kSlotsPerLine) {
+        const int64_t nlines = (cap + kSlotsPerLine - 1) / kSlotsPerLine;
+        const int64_t slot = lines.grow(nlines) * kSlotsPerLine;
+        const int32_t left = (int32_t)(nlines * kSlotsPerLine - cap);
+        if (left > 0) {
+            if (partial_.size() >= 64) partial_.erase(partial_.begin());
+            partial_.push_back({slot + cap, left});
+        }
+        return slot;
+    }
+    if (cfg_.node_slab) {
+        // the node's own line: its first blocks (capacities 1, 1, 2, 4 under the adaptive rule)
+        // end up next to each other, so the walk reads one line for all of them
+        uint32_t& sl = slab_line_[(size_t)nidx];
+        uint8_t& used = slab_used_[(size_t)nidx];
+        if (sl == 0) {
+            const int64_t line = lines.grow(1);
+            if (line + 1 > (int64_t)UINT32_MAX) throw std::bad_alloc();
+            sl = (uint32_t)(line + 1);
+            used = 0;
+        }
+        if (used + cap <= kSlotsPerLine) {
+            const int64_t slot = (int64_t)(sl - 1) * kSlotsPerLine + used;
+            used = (uint8_t)(used + cap);
+            return slot;
+        }
+    }
+    for (size_t i = 0; i < partial_.size(); ++i)
+        if (partial_[i].free >= cap) {
+            const int64_t slot = partial_[i].slot;
+            partial_[i].slot += cap;
+            partial_[i].free -= (int32_t)cap;
+            if (partial_[i].free == 0) partial_.erase(partial_.begin() + (long)i);
+            return slot;
+        }
+    const int64_t slot = lines.grow(1) * kSlotsPerLine;
+    if (partial_.size() >= 64) partial_.erase(partial_.begin());
+    partial_.push_back({slot + cap, (int32_t)(kSlotsPerLine - cap)});
+    return slot;
 }
 
 const BlockRec& Store::block_of(int64_t nidx, int32_t i) const {
@@ -153,7 +199,7 @@ int Store::add_edges(int32_t inst, const int32_t* src, const int32_t* dst, const
     for (const InstanceTotals& t : totals_) stored += t.edges;
     const int64_t by_tau = m * std::max<int64_t>(1, cfg_.tau);   // m, tau < 2^31: no overflow
     const int64_t worst_new_slots = m + (cfg_.sizing == TNS_SIZING_FIXED ? by_tau : std::min(by_tau, stored + m));
-    if (edges.size() + worst_new_slots > kMaxEdgeOffset) {
+    if (lines.size() * kSlotsPerLine + worst_new_slots + 2 * kSlotsPerLine * m > kMaxEdgeOffset) {
         err = "edge array would exceed 2^40 slots";
         return TNS_ESIZE;
     }
@@ -168,7 +214,7 @@ int Store::add_edges(int32_t inst, const int32_t* src, const int32_t* dst, const
         NodeLine& nd = nodes.mut(nidx);
         int64_t i = g0;
         auto put = [&](int64_t pos, uint32_t e) {
-            Edge& ed = edges.raw(pos);
+            Edge& ed = edge_at(pos);
             ed.ts = ts[e];
             ed.nbr = dst[e];
             ed.eid = eid ? eid[e] : (int32_t)(eid_base + (int64_t)e);
@@ -180,7 +226,7 @@ int Store::add_edges(int32_t inst, const int32_t* src, const int32_t* dst, const
             const int64_t take = std::min<int64_t>(tail_cap_[(size_t)nidx] - size, g1 - i);
             if (take > 0) {
                 for (int64_t k = 0; k < take; ++k) put(off + size + k, ord[i + k]);
-                edges.mark(off + size, take);
+                mark_slots(off + size, take);
                 tb = make_rec(tb.t_min, ts[ord[i + take - 1]], off, size + (int32_t)take);
                 nd.degree += (int32_t)take;
                 i += take;
@@ -194,9 +240,9 @@ int Store::add_edges(int32_t inst, const int32_t* src, const int32_t* dst, const
             else cap = std::max<int64_t>(rest, std::min<int64_t>(nd.degree, cfg_.tau));  // b_v = min(deg(v), tau)
             cap = std::min(cap, kMaxBlockEdges);   // limit of the record's size field
             const int64_t take = std::min(rest, cap);
-            const int64_t off = edges.grow(cap);
+            const int64_t off = place_block(nidx, cap);
             for (int64_t k = 0; k < take; ++k) put(off + k, ord[i + k]);
-            edges.mark(off, cap);
+            mark_slots(off, take);
             append_block(nidx, nd, make_rec(ts[ord[i]], ts[ord[i + take - 1]], off, (int32_t)take), (int32_t)cap);
             nd.degree += (int32_t)take;
             tot.slots += cap;

@@ -90,10 +90,11 @@ struct StoreConfig {
     int32_t num_instances = 1;
     int32_t tau = 1;
     int32_t sizing = 0;  // 0 adaptive, 1 strawman, 2 fixed
+    bool node_slab = true;  // give each node one edge line of its own for its first blocks
 };
 
 struct InstanceTotals {
-    int64_t edges = 0, slots = 0, blocks = 0, next_eid = 0;
+    int64_t edges = 0, slots = 0, blocks = 0, next_eid = 0;   // slots: sum of block capacities
     float newest_ts = 0.0f;  // newest timestamp stored so far (valid if edges > 0)
 };
 
@@ -114,9 +115,22 @@ public:
 
     Paged<NodeLine, 18, 9> nodes;   // 128-byte entries: 2^18 per page, change tracking per 64 KiB
     Paged<BlockRec> dir;            // directory pool: record runs of nodes with long lists
-    Paged<Edge> edges;
+    Paged<EdgeLine, 18, 9> lines;   // edge data, 10 slots per 128-byte line
+
+    Edge& edge_at(int64_t slot) { return lines.raw(slot / kSlotsPerLine).e[slot % kSlotsPerLine]; }
+    void mark_slots(int64_t slot, int64_t count) {
+        if (count > 0) lines.mark(slot / kSlotsPerLine, (slot + count - 1) / kSlotsPerLine - slot / kSlotsPerLine + 1);
+    }
 
 private:
+    // Placement of a new block's slots.  Blocks of 10 slots or more start on a line; smaller
+    // ones go to the node's own line while it has room (node_slab), else into the leftover of
+    // some line, never across a line boundary.
+    int64_t place_block(int64_t nidx, int64_t cap);
+    struct Partial { int64_t slot; int32_t free; };
+    std::vector<Partial> partial_;        // lines with unused slots at their end (bounded list)
+    std::vector<uint32_t> slab_line_;     // node's own line + 1 (0: none yet)
+    std::vector<uint8_t> slab_used_;      // slots of it already given to blocks
     BlockRec& tail_rec(NodeLine& nd);
     void append_block(int64_t nidx, NodeLine& nd, const BlockRec& r, int32_t cap);
 

@@ -95,7 +95,9 @@ def test_sizing_closed_forms():
     assert list(B.tns_node_blocks(h, 0, 0)["cap"]) == [5, 5, 28, 8]
     st = B.tns_stats(h)
     assert st["wasted_slots"] == 7 and st["num_edges"] == 39 and st["max_list_len"] == 4
-    assert st["edge_data_bytes"] == 46 * 12 and st["metadata_bytes"] == 2 * 128      # two node lines, no directory run
+    # edge lines of 10 slots: the two 5-slot blocks share the node's own line, 28 slots take 3 lines,
+    # the 8-slot block a line of its own; two node lines, no directory run
+    assert st["edge_data_bytes"] == 5 * 128 and st["metadata_bytes"] == 2 * 128
     B.tns_destroy(h)
 
 

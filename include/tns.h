@@ -85,6 +85,13 @@ typedef struct {
 TNS_API int tns_plan_create(const tns_config *cfg, tns_plan **out);
 
 /*
+ * Change the sampler settings of an existing plan without touching the store (the paper keeps
+ * the dynamic graph and the sampler apart: one graph can serve samplers with different fan-outs
+ * and policies).  Same value ranges as in tns_config; takes effect for the next tns_run.
+ */
+TNS_API int tns_set_sampler(tns_plan *plan, int32_t fanout, int32_t policy, int32_t inclusive_end, uint64_t seed);
+
+/*
  * Ingest one batch of m edges into instance `instance` (section 4.1, edge insertion: append
  * to the node's tail block while it has room, otherwise link a new block at the tail; the
  * new block's capacity is max(remaining edges of this batch for the node,

@@ -22,7 +22,7 @@ TNS_MAX_FANOUT = 64
 TNS_FLAG_NO_XCD_REMAP = 1
 TNS_FLAG_NO_NODE_SLAB = 2
 
-EXPORTS = ["tns_plan_create", "tns_add_edges", "tns_commit", "tns_workspace", "tns_run", "tns_compact", "tns_traffic_model", "tns_stats",
+EXPORTS = ["tns_plan_create", "tns_set_sampler", "tns_add_edges", "tns_commit", "tns_workspace", "tns_run", "tns_compact", "tns_traffic_model", "tns_stats",
            "tns_node_blocks", "tns_destroy", "tns_strerror", "tns_last_error"]
 
 
@@ -60,6 +60,8 @@ def lib():
         vp, i32p, i64p, f32p = C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_float)
         L.tns_plan_create.argtypes = [C.POINTER(tns_config), C.POINTER(vp)]
         L.tns_plan_create.restype = C.c_int
+        L.tns_set_sampler.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_uint64]
+        L.tns_set_sampler.restype = C.c_int
         L.tns_add_edges.argtypes = [vp, C.c_int32, i32p, i32p, f32p, i32p, C.c_int64]
         L.tns_add_edges.restype = C.c_int
         L.tns_commit.argtypes = [vp, vp]
@@ -109,6 +111,10 @@ def tns_plan_create(num_nodes: int, fanout: int, policy: int = TNS_POLICY_RECENT
     h = C.c_void_p()
     _check(lib().tns_plan_create(C.byref(cfg), C.byref(h)), "tns_plan_create")
     return h
+
+
+def tns_set_sampler(plan, fanout: int, policy: int = TNS_POLICY_RECENT, inclusive_end: int = 0, seed: int = 0) -> None:
+    _check(lib().tns_set_sampler(plan, fanout, policy, inclusive_end, seed), "tns_set_sampler")
 
 
 def tns_add_edges(plan, instance: int, src, dst, ts, eid=None) -> None:
@@ -198,6 +204,10 @@ class Plan:
     @property
     def handle(self):
         return self._h
+
+    def set_sampler(self, fanout: int, policy: int = TNS_POLICY_RECENT, inclusive_end: int = 0, seed: int = 0):
+        tns_set_sampler(self._h, fanout, policy, inclusive_end, seed)
+        self.fanout = fanout
 
     def add_edges(self, src, dst, ts, eid=None, instance: int = 0):
         tns_add_edges(self._h, instance, src, dst, ts, eid)

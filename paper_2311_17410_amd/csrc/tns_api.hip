@@ -2,6 +2,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <memory>
 #include <new>
@@ -133,6 +134,19 @@ int tns_plan_create(const tns_config* cfg, tns_plan** out) {
     return TNS_OK;
 }
 
+int tns_set_sampler(tns_plan* plan, int32_t fanout, int32_t policy, int32_t inclusive_end, uint64_t seed) {
+    g_err.clear();
+    if (!plan) return fail(TNS_EINVAL, "null plan");
+    if (fanout < 1 || fanout > TNS_MAX_FANOUT) return fail(TNS_EINVAL, "fanout must be in [1, 64]");
+    if (policy != TNS_POLICY_RECENT && policy != TNS_POLICY_UNIFORM) return fail(TNS_EINVAL, "unknown policy");
+    if (inclusive_end != 0 && inclusive_end != 1) return fail(TNS_EINVAL, "inclusive_end must be 0 or 1");
+    plan->cfg.fanout = fanout;
+    plan->cfg.policy = policy;
+    plan->cfg.inclusive_end = inclusive_end;
+    plan->cfg.seed = seed;
+    return TNS_OK;
+}
+
 int tns_add_edges(tns_plan* plan, int32_t instance, const int32_t* src, const int32_t* dst, const float* ts,
                   const int32_t* eid, int64_t m) {
     g_err.clear();
@@ -261,11 +275,15 @@ int tns_run(tns_plan* plan, int64_t Q, const int32_t* d_targets, const float* d_
     a.out_eid = d_out_eid;
     a.out_ts = d_out_ts;
     a.out_count = d_out_count;
+    if (want_cmp) {   // one pass: sampling with the padding removal fused in
+        a.scan_ws = d_workspace;
+        a.rowptr = d_rowptr;
+        a.cmp_nbr = d_cmp_nbr;
+        a.cmp_eid = d_cmp_eid;
+        a.cmp_ts = d_cmp_ts;
+    }
     const hipError_t e = tns::launch_sample(a, stream);
     if (e != hipSuccess) return fail_hip(e, "launching the sampling kernel");
-    if (want_cmp)
-        return run_compact(plan, Q, d_out_nbr, d_out_eid, d_out_ts, d_out_count, d_rowptr, d_cmp_nbr, d_cmp_eid,
-                           d_cmp_ts, d_workspace, stream);
     return TNS_OK;
 }
 

@@ -27,6 +27,13 @@ struct SampleArgs {
     // non-null: count what the walk reads (node entries, block records, timestamp probes,
     // edges selected) into counters[0..3] instead of producing outputs
     unsigned long long* counters;
+    // non-null: also remove the padding in the same pass (chained scan over workgroups);
+    // scan_ws is the caller's workspace, rowptr / cmp_* the dense outputs
+    void* scan_ws;
+    int64_t* rowptr;
+    int32_t* cmp_nbr;
+    int32_t* cmp_eid;
+    float* cmp_ts;
     int64_t Q;
     int64_t num_nodes;
     int64_t num_dir;     // records in the directory pool (walks never index past it)

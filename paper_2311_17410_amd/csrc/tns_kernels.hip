@@ -13,6 +13,7 @@
 #include "tns_kernels.h"
 
 #include <algorithm>
+#include <cstdlib>
 
 namespace tns {
 namespace {
@@ -41,6 +42,74 @@ __device__ __forceinline__ uint64_t pick_rank(uint64_t seed, int64_t qid, int32_
     z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
     z ^= z >> 31;
     return ((z >> 32) * c) >> 32;
+}
+
+__device__ __forceinline__ int32_t wave_inclusive_scan(int32_t v, int lane) {
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int32_t u = __shfl_up(v, d, kWave);
+        if (lane >= d) v += u;
+    }
+    return v;
+}
+
+// ---- single-pass chained scan over workgroup tiles (padding removal fused into sampling) ----
+//
+// Workspace layout: word 0 = tile ticket, word 1 = error flag, then one 64-bit status per tile:
+// bits 62-63 = state (0 not ready, 1 tile total, 2 inclusive prefix), bits 0-61 = value.
+// Tiles take their index from the ticket, so a tile only ever waits for tiles that have
+// already started; the wait is bounded and sets the error flag if the bound is ever hit.
+constexpr uint64_t kStTotal = 1ull << 62, kStPrefix = 2ull << 62, kStMask = 3ull << 62;
+constexpr int kSpinLimit = 1 << 22;
+constexpr int kFusedRegSlots = 10;   // fan-outs up to this keep the gathered edges in registers (fused variant)
+
+struct ScanWorkspace {
+    uint32_t ticket;
+    uint32_t error;
+    uint32_t pad[62];
+    uint64_t status[1];   // [number of tiles]
+};
+
+// Sum of the totals of all tiles before `tile` (called by one whole wave).
+__device__ __forceinline__ int64_t lookback_exclusive(ScanWorkspace* ws, int64_t tile, int lane) {
+    int64_t excl = 0;
+    int64_t idx = tile - 1;
+    int spins = 0;
+    while (true) {
+        const int64_t t = idx - lane;
+        uint64_t st = kStPrefix;   // before the first tile: prefix 0
+        if (t >= 0) st = __hip_atomic_load(&ws->status[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint64_t state = st & kStMask;
+        const uint64_t is_prefix = __ballot(state == kStPrefix);
+        const uint64_t not_ready = __ballot(state == 0);
+        const int first = is_prefix ? __builtin_ctzll(is_prefix) : kWave;             // nearest tile with a full prefix
+        const uint64_t needed = first >= kWave - 1 ? ~0ull : ((2ull << first) - 1);    // lanes 0..first
+        if (not_ready & needed) {
+            if (++spins > kSpinLimit) {
+                if (lane == 0) atomicExch(&ws->error, 1u);
+                return excl;
+            }
+            __builtin_amdgcn_s_sleep(2);
+            continue;
+        }
+        int64_t v = (lane <= first) ? (int64_t)(st & ~kStMask) : 0;
+        for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, kWave);
+        excl += v;
+        if (first < kWave) return excl;
+        idx -= kWave;
+    }
+}
+
+// Clears the ticket, the error flag and the tile states before a fused launch (a kernel rather
+// than a memset, so that the launch sequence can be captured into a graph).
+__global__ void __launch_bounds__(256) tns_scan_init(ScanWorkspace* ws, int64_t num_tiles, int64_t* rowptr0, int64_t Q) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i == 0) {
+        ws->ticket = 0;
+        ws->error = 0;
+        if (Q == 0) rowptr0[0] = 0;
+    }
+    if (i < num_tiles) ws->status[i] = 0;
 }
 
 // State of one lane's walk over the blocks of its target node, newest block first
@@ -135,15 +204,29 @@ __device__ __forceinline__ BlockRec as_rec(const uint4& u) {
     return r;
 }
 
-template <int POLICY, bool INCL, typename pos_t, bool COUNT>
-__global__ void __launch_bounds__(256) tns_sample_kernel(const SampleArgs p, const int32_t stride,
+// FUSED: also removes the padding in the same pass (rowptr and dense arrays), with the tile
+// offsets obtained from a chained scan over the workgroups.
+template <int POLICY, bool INCL, typename pos_t, bool COUNT, bool FUSED>
+__global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const SampleArgs p, const int32_t stride,
                                                          const uint32_t f_magic) {
     extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ int64_t s_tile_base;
+    __shared__ int32_t s_wave_sum[16];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
     const int waves_per_wg = blockDim.x >> 6;
 
-    const int64_t tile = p.xcd_remap ? xcd_tile(blockIdx.x, gridDim.x) : (int64_t)blockIdx.x;
+    int64_t tile;
+    if (FUSED) {
+        // tiles are numbered in the order workgroups start
+        ScanWorkspace* ws = static_cast<ScanWorkspace*>(p.scan_ws);
+        if (threadIdx.x == 0) s_tile_base = (int64_t)atomicAdd(&ws->ticket, 1u);
+        __syncthreads();
+        tile = s_tile_base;
+        __syncthreads();
+    } else {
+        tile = p.xcd_remap ? xcd_tile(blockIdx.x, gridDim.x) : (int64_t)blockIdx.x;
+    }
     const int64_t q0 = (tile * waves_per_wg + wave) * kWave;
     const int64_t q = q0 + lane;
     const int32_t f = p.fanout;
@@ -229,42 +312,141 @@ __global__ void __launch_bounds__(256) tns_sample_kernel(const SampleArgs p, con
         }
         return;
     }
-    __syncthreads();
-
-    // cooperative gather + padded write: the wave's 64*f slots in flat order
     const pos_t* __restrict__ w_pos = reinterpret_cast<const pos_t*>(smem) + (size_t)wave * kWave * stride;
     const int64_t out0 = q0 * f;
-    for (int32_t it = 0; it < f; ++it) {
-        const uint32_t s = (uint32_t)(it * kWave + lane);
-        const uint32_t ql = div_by(s, (uint32_t)f, f_magic);
-        const int32_t j = (int32_t)(s - ql * (uint32_t)f);
-        const int32_t kq = __shfl(k, (int)ql, kWave);
-        if (q0 + (int64_t)ql < p.Q) {
-            int32_t nbr = -1, eid = -1;
-            float t = 0.0f;
-            if (j < kq) {
-                const int64_t pos = (int64_t)w_pos[ql * stride + j];
-                const Edge e = *reinterpret_cast<const Edge*>(p.edges + pos);
-                nbr = e.nbr; eid = e.eid; t = e.ts;
+
+    if (FUSED) {
+        // Chained scan over the workgroup tiles for the dense offsets.
+        ScanWorkspace* ws = static_cast<ScanWorkspace*>(p.scan_ws);
+        const int32_t inc = wave_inclusive_scan(k, lane);
+        if (lane == kWave - 1) s_wave_sum[wave] = inc;
+        __syncthreads();
+        int32_t wave_off = 0, wg_total = 0;
+        for (int i = 0; i < waves_per_wg; ++i) {
+            const int32_t t = s_wave_sum[i];
+            if (i < wave) wave_off += t;
+            wg_total += t;
+        }
+        auto chain = [&]() {      // wave 0: publish the tile total, look back, publish the prefix
+            if (lane == 0 && tile > 0)
+                __hip_atomic_store(&ws->status[tile], kStTotal | (uint64_t)wg_total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int64_t excl = tile > 0 ? lookback_exclusive(ws, tile, lane) : 0;
+            if (lane == 0) {
+                __hip_atomic_store(&ws->status[tile], kStPrefix | (uint64_t)(excl + wg_total), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+                s_tile_base = excl;
             }
-            p.out_nbr[out0 + s] = nbr;
-            p.out_eid[out0 + s] = eid;
-            p.out_ts[out0 + s] = t;
+        };
+        // one loop that gathers and writes both the padded row and the dense copy; needs the tile offset
+        auto gather_both = [&]() {
+            const int64_t row = s_tile_base + wave_off + (inc - k);
+            if (q < p.Q) {
+                p.rowptr[q] = row;
+                if (q == p.Q - 1) p.rowptr[p.Q] = row + k;
+            }
+            for (int32_t it = 0; it < f; ++it) {
+                const uint32_t s = (uint32_t)(it * kWave + lane);
+                const uint32_t ql = div_by(s, (uint32_t)f, f_magic);
+                const int32_t j = (int32_t)(s - ql * (uint32_t)f);
+                const int32_t kq = __shfl(k, (int)ql, kWave);
+                const int64_t rowq = __shfl(row, (int)ql, kWave);
+                if (q0 + (int64_t)ql < p.Q) {
+                    int32_t nbr = -1, eid = -1;
+                    float t = 0.0f;
+                    if (j < kq) {
+                        const int64_t pos = (int64_t)w_pos[ql * stride + j];
+                        const Edge e = *reinterpret_cast<const Edge*>(p.edges + pos);
+                        nbr = e.nbr; eid = e.eid; t = e.ts;
+                        p.cmp_nbr[rowq + j] = nbr;
+                        p.cmp_eid[rowq + j] = eid;
+                        p.cmp_ts[rowq + j] = t;
+                    }
+                    p.out_nbr[out0 + s] = nbr;
+                    p.out_eid[out0 + s] = eid;
+                    p.out_ts[out0 + s] = t;
+                }
+            }
+        };
+        if (f <= kFusedRegSlots) {
+            // While wave 0 resolves the tile offset, the other waves already gather and write
+            // their padded rows; the gathered edges stay in registers and only the dense copy
+            // waits for the offset.
+            if (wave == 0) chain();
+            int32_t vn[kFusedRegSlots], ve[kFusedRegSlots];
+            float vt[kFusedRegSlots];
+#pragma unroll
+            for (int it = 0; it < kFusedRegSlots; ++it) {
+                vn[it] = -1; ve[it] = -1; vt[it] = 0.0f;
+                if (it < f) {
+                    const uint32_t s = (uint32_t)(it * kWave + lane);
+                    const uint32_t ql = div_by(s, (uint32_t)f, f_magic);
+                    const int32_t j = (int32_t)(s - ql * (uint32_t)f);
+                    const int32_t kq = __shfl(k, (int)ql, kWave);
+                    if (j < kq) {
+                        const int64_t pos = (int64_t)w_pos[ql * stride + j];
+                        const Edge e = *reinterpret_cast<const Edge*>(p.edges + pos);
+                        vn[it] = e.nbr; ve[it] = e.eid; vt[it] = e.ts;
+                    }
+                    if (q0 + (int64_t)ql < p.Q) {
+                        p.out_nbr[out0 + s] = vn[it];
+                        p.out_eid[out0 + s] = ve[it];
+                        p.out_ts[out0 + s] = vt[it];
+                    }
+                }
+            }
+            __syncthreads();
+            const int64_t row = s_tile_base + wave_off + (inc - k);
+            if (q < p.Q) {
+                p.rowptr[q] = row;
+                if (q == p.Q - 1) p.rowptr[p.Q] = row + k;
+            }
+#pragma unroll
+            for (int it = 0; it < kFusedRegSlots; ++it) {
+                if (it < f) {
+                    const uint32_t s = (uint32_t)(it * kWave + lane);
+                    const uint32_t ql = div_by(s, (uint32_t)f, f_magic);
+                    const int32_t j = (int32_t)(s - ql * (uint32_t)f);
+                    const int32_t kq = __shfl(k, (int)ql, kWave);
+                    const int64_t rowq = __shfl(row, (int)ql, kWave);
+                    if (j < kq) {       // consecutive lanes write consecutive dense entries
+                        p.cmp_nbr[rowq + j] = vn[it];
+                        p.cmp_eid[rowq + j] = ve[it];
+                        p.cmp_ts[rowq + j] = vt[it];
+                    }
+                }
+            }
+        } else {
+            // larger fan-outs: offset first, then one loop gathers and writes both
+            if (wave == 0) chain();
+            __syncthreads();
+            gather_both();
+        }
+    } else {
+        __syncthreads();
+        // cooperative gather + padded write: the wave's 64*f slots in flat order
+        for (int32_t it = 0; it < f; ++it) {
+            const uint32_t s = (uint32_t)(it * kWave + lane);
+            const uint32_t ql = div_by(s, (uint32_t)f, f_magic);
+            const int32_t j = (int32_t)(s - ql * (uint32_t)f);
+            const int32_t kq = __shfl(k, (int)ql, kWave);
+            if (q0 + (int64_t)ql < p.Q) {
+                int32_t nbr = -1, eid = -1;
+                float t = 0.0f;
+                if (j < kq) {
+                    const int64_t pos = (int64_t)w_pos[ql * stride + j];
+                    const Edge e = *reinterpret_cast<const Edge*>(p.edges + pos);
+                    nbr = e.nbr; eid = e.eid; t = e.ts;
+                }
+                p.out_nbr[out0 + s] = nbr;
+                p.out_eid[out0 + s] = eid;
+                p.out_ts[out0 + s] = t;
+            }
         }
     }
     if (q < p.Q) p.out_count[q] = k;
 }
 
 // ---- padding removal -------------------------------------------------------------------
-
-__device__ __forceinline__ int32_t wave_inclusive_scan(int32_t v, int lane) {
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const int32_t u = __shfl_up(v, d, kWave);
-        if (lane >= d) v += u;
-    }
-    return v;
-}
 
 // sum of counts per tile of kCompactTile queries
 __global__ void __launch_bounds__(256) tns_count_tile_sums(const int32_t* __restrict__ count, int64_t Q,
@@ -366,39 +548,51 @@ __global__ void __launch_bounds__(256) tns_compact_scatter(const CompactArgs a, 
 
 inline uint32_t magic_for(int32_t f) { return f <= 1 ? 0u : (uint32_t)(((uint64_t(1) << 32) + (uint64_t)f - 1) / (uint64_t)f); }
 
-template <int POLICY, bool INCL, typename pos_t, bool COUNT>
+template <int POLICY, bool INCL, typename pos_t, bool COUNT, bool FUSED>
 hipError_t launch_sample_t(const SampleArgs& a, hipStream_t stream) {
     const int32_t stride = a.fanout | 1;                                    // odd: conflict-free per-lane rows
     const size_t per_wave = (size_t)kWave * stride * sizeof(pos_t);
-    int waves = (int)std::min<size_t>(4, std::max<size_t>(1, (48u << 10) / per_wave));
+    // The fused variant uses large workgroups: one chained-scan step per 1024 queries keeps the
+    // rate at which tiles publish their totals low enough for the look-back to keep up.
+    int waves = (int)std::min<size_t>(FUSED ? 16 : 4, std::max<size_t>(1, (48u << 10) / per_wave));
     const int64_t per_wg = (int64_t)waves * kWave;
     const int64_t grid = (a.Q + per_wg - 1) / per_wg;
-    if (grid <= 0) return hipSuccess;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((tns_sample_kernel<POLICY, INCL, pos_t, COUNT>), dim3((unsigned)grid), dim3(waves * kWave),
-                       per_wave * waves, stream, a, stride, magic_for(a.fanout));
+    if (FUSED) {
+        const unsigned init_grid = (unsigned)std::max<int64_t>(1, (grid + 255) / 256);
+        hipLaunchKernelGGL(tns_scan_init, dim3(init_grid), dim3(256), 0, stream, static_cast<ScanWorkspace*>(a.scan_ws),
+                           grid, a.rowptr, a.Q);
+    }
+    if (grid <= 0) return hipGetLastError();
+    const size_t lds = per_wave * waves;
+    hipLaunchKernelGGL((tns_sample_kernel<POLICY, INCL, pos_t, COUNT, FUSED>), dim3((unsigned)grid), dim3(waves * kWave),
+                       lds, stream, a, stride, magic_for(a.fanout));
     return hipGetLastError();
 }
 
 }  // namespace
 
 size_t compact_workspace_bytes(int64_t Q) {
+    // enough for either use: tile sums + offsets of the stand-alone compaction, or the ticket
+    // and one state per 64-query wave (the smallest workgroup) of the fused chained scan
     const int64_t tiles = (Q + kCompactTile - 1) / kCompactTile;
     const size_t sums = ((size_t)tiles * sizeof(int32_t) + 255) & ~size_t(255);
     const size_t offs = ((size_t)tiles * sizeof(int64_t) + 255) & ~size_t(255);
-    return sums + offs + 256;
+    const size_t fused = 256 + (size_t)((Q + kWave - 1) / kWave + 1) * sizeof(uint64_t);
+    return std::max(sums + offs + 256, (fused + 255) & ~size_t(255));
 }
 
 hipError_t launch_sample(const SampleArgs& a, hipStream_t stream) {
     const bool incl = a.inclusive_end != 0;
     const bool wide = a.wide_offsets != 0;
-#define TNS_DISPATCH(POL, CNT)                                                          \
-    (incl ? (wide ? launch_sample_t<POL, true, int64_t, CNT>(a, stream)                 \
-                  : launch_sample_t<POL, true, int32_t, CNT>(a, stream))                \
-          : (wide ? launch_sample_t<POL, false, int64_t, CNT>(a, stream)                \
-                  : launch_sample_t<POL, false, int32_t, CNT>(a, stream)))
-    if (a.counters) return a.policy == 0 ? TNS_DISPATCH(0, true) : TNS_DISPATCH(1, true);
-    return a.policy == 0 ? TNS_DISPATCH(0, false) : TNS_DISPATCH(1, false);
+#define TNS_DISPATCH(POL, CNT, FUS)                                                          \
+    (incl ? (wide ? launch_sample_t<POL, true, int64_t, CNT, FUS>(a, stream)                 \
+                  : launch_sample_t<POL, true, int32_t, CNT, FUS>(a, stream))                \
+          : (wide ? launch_sample_t<POL, false, int64_t, CNT, FUS>(a, stream)                \
+                  : launch_sample_t<POL, false, int32_t, CNT, FUS>(a, stream)))
+    if (a.counters) return a.policy == 0 ? TNS_DISPATCH(0, true, false) : TNS_DISPATCH(1, true, false);
+    if (a.scan_ws) return a.policy == 0 ? TNS_DISPATCH(0, false, true) : TNS_DISPATCH(1, false, true);
+    return a.policy == 0 ? TNS_DISPATCH(0, false, false) : TNS_DISPATCH(1, false, false);
 #undef TNS_DISPATCH
 }
 

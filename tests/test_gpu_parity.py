@@ -133,6 +133,34 @@ def test_query_id_base_and_chunked_runs(B, oracle_lib):
     plan.close()
 
 
+def test_standalone_compaction_equals_fused(B, oracle_lib):
+    import torch
+    st = W.tiny_stream(81, 6000, 50, 512, ties=True)
+    wl = wl_of(st, fanout=7)
+    plan = build_plan(B, wl)
+    targets, t_start, t_end = W.random_queries(82, st, 5000 + 13)
+    fused = gpu_sample(plan, targets, t_start, t_end)                 # tns_run with the dense outputs
+    ref = oracle_sample(oracle_lib, wl, targets, t_start, t_end, None, 7, 0, 0, 0)
+    assert_same(fused, ref, oracle_lib, "fused")
+    # the same through tns_run (padded only) + tns_compact
+    dev = torch.device("cuda", 0)
+    Q = len(targets)
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    dt, dtb, dte = d(targets), d(t_start), d(t_end)
+    out = plan.alloc_outputs(Q, compact=True)
+    p = lambda t: t.data_ptr()
+    B.tns_run(plan.handle, Q, p(dt), p(dtb), p(dte), 0, 0, p(out["nbr"]), p(out["eid"]), p(out["ts"]), p(out["count"]))
+    B.tns_compact(plan.handle, Q, p(out["nbr"]), p(out["eid"]), p(out["ts"]), p(out["count"]), p(out["rowptr"]),
+                  p(out["cmp_nbr"]), p(out["cmp_eid"]), p(out["cmp_ts"]), p(out["workspace"]), out["workspace"].numel())
+    torch.cuda.synchronize()
+    total = int(out["rowptr"][-1].item())
+    assert np.array_equal(out["rowptr"].cpu().numpy(), fused["rowptr"])
+    for k in ("cmp_nbr", "cmp_eid"):
+        assert np.array_equal(out[k][:total].cpu().numpy(), fused[k])
+    assert np.array_equal(out["cmp_ts"][:total].cpu().numpy().view(np.int32), fused["cmp_ts"].view(np.int32))
+    plan.close()
+
+
 # ---- the configurations --------------------------------------------------------------------
 
 def _check_config(B, oracle, wl, threads=16, window=True, policies=(0, 1)):

@@ -152,6 +152,40 @@ TNS_API int tns_run(tns_plan *plan, int64_t Q, const int32_t *d_targets, const f
             void *d_workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Multi-hop sampling (section 4.2: the process is repeated per layer, the nodes sampled in one
+ * layer being the targets of the next).  Hop 1 samples the given queries exactly as tns_run;
+ * hop h+1 has one query per dense entry of hop h, in dense order: target = the sampled
+ * neighbour, window end = the timestamp of the sampled edge, window start = end - delta
+ * (delta = +infinity: unbounded).  A temporal random walk is the special case fanouts = 1,1,...
+ *
+ *   fanouts[num_hops]   HOST; each in 1..TNS_MAX_FANOUT (the plan's own fan-out is not used)
+ *   hops[num_hops]      HOST array of DEVICE buffer sets, all fields required.  With
+ *                       cap_1 = Q and cap_{h+1} = cap_h * fanouts[h] (the most queries hop h can
+ *                       have), hop h needs nbr/eid/ts[cap_h * fanouts[h]], count[cap_h],
+ *                       rowptr[cap_h + 1], cmp_nbr/eid/ts[cap_h * fanouts[h]].  Only the entries
+ *                       of the hop's actual queries are written; their number n_h is
+ *                       rowptr_{h-1}[n_{h-1}] (n_1 = Q) and rowptr_h[n_h] closes the hop.
+ *   query ids (uniform policy): hop h numbers its queries from
+ *                       query_id_base + cap_1 + ... + cap_{h-1}
+ *   d_workspace         at least tns_workspace_khop() bytes, 256-byte aligned
+ * Nothing is copied to the host between hops; the whole sequence is queued on the stream.
+ */
+typedef struct {
+    int32_t *nbr, *eid;
+    float *ts;
+    int32_t *count;
+    int64_t *rowptr;
+    int32_t *cmp_nbr, *cmp_eid;
+    float *cmp_ts;
+} tns_hop_buffers;
+TNS_API int tns_workspace_khop(const tns_plan *plan, int32_t num_hops, const int32_t *fanouts, int64_t Q,
+                               size_t *bytes);
+TNS_API int tns_run_khop(tns_plan *plan, int32_t num_hops, const int32_t *fanouts, float delta, int64_t Q,
+                         const int32_t *d_targets, const float *d_t_start, const float *d_t_end,
+                         const int64_t *d_inst_rowptr, int64_t query_id_base, const tns_hop_buffers *hops,
+                         void *d_workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Padding removal alone (section 5: after each sampling kernel the invalid neighbours are
  * removed): the second half of tns_run, for callers that keep the two steps apart.  Reads the
  * padded arrays and counts written by tns_run (DEVICE, same layout) and writes d_rowptr[Q+1]

@@ -22,7 +22,7 @@ TNS_MAX_FANOUT = 64
 TNS_FLAG_NO_XCD_REMAP = 1
 TNS_FLAG_NO_NODE_SLAB = 2
 
-EXPORTS = ["tns_plan_create", "tns_set_sampler", "tns_add_edges", "tns_commit", "tns_workspace", "tns_run", "tns_compact", "tns_traffic_model", "tns_stats",
+EXPORTS = ["tns_plan_create", "tns_set_sampler", "tns_add_edges", "tns_commit", "tns_workspace", "tns_run", "tns_workspace_khop", "tns_run_khop", "tns_compact", "tns_traffic_model", "tns_stats",
            "tns_node_blocks", "tns_destroy", "tns_strerror", "tns_last_error"]
 
 
@@ -36,6 +36,10 @@ class tns_stats_t(C.Structure):
     _fields_ = [("avg_list_len", C.c_double), ("max_list_len", C.c_int64), ("edge_data_bytes", C.c_int64),
                 ("metadata_bytes", C.c_int64), ("wasted_slots", C.c_int64), ("num_blocks", C.c_int64),
                 ("num_edges", C.c_int64)]
+
+
+class tns_hop_buffers(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("nbr", "eid", "ts", "count", "rowptr", "cmp_nbr", "cmp_eid", "cmp_ts")]
 
 
 class TnsError(RuntimeError):
@@ -71,6 +75,11 @@ def lib():
         L.tns_run.argtypes = [vp, C.c_int64, vp, vp, vp, vp, C.c_int64, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                               C.c_size_t, vp]
         L.tns_run.restype = C.c_int
+        L.tns_workspace_khop.argtypes = [vp, C.c_int32, i32p, C.c_int64, C.POINTER(C.c_size_t)]
+        L.tns_workspace_khop.restype = C.c_int
+        L.tns_run_khop.argtypes = [vp, C.c_int32, i32p, C.c_float, C.c_int64, vp, vp, vp, vp, C.c_int64,
+                                   C.POINTER(tns_hop_buffers), vp, C.c_size_t, vp]
+        L.tns_run_khop.restype = C.c_int
         L.tns_compact.argtypes = [vp, C.c_int64, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.tns_compact.restype = C.c_int
         L.tns_traffic_model.argtypes = [vp, C.c_int64, vp, vp, vp, vp, C.c_int64, vp, vp]
@@ -148,6 +157,27 @@ def tns_run(plan, Q: int, d_targets: int, d_t_start: int, d_t_end: int, d_inst_r
                          vp(d_cmp_eid), vp(d_cmp_ts), vp(d_workspace), workspace_bytes, vp(hip_stream)), "tns_run")
 
 
+def tns_workspace_khop(plan, fanouts, Q: int) -> int:
+    fo = (C.c_int32 * len(fanouts))(*fanouts)
+    n = C.c_size_t()
+    _check(lib().tns_workspace_khop(plan, len(fanouts), fo, Q, C.byref(n)), "tns_workspace_khop")
+    return int(n.value)
+
+
+def tns_run_khop(plan, fanouts, delta: float, Q: int, d_targets: int, d_t_start: int, d_t_end: int, d_inst_rowptr: int,
+                 query_id_base: int, hops, d_workspace: int, workspace_bytes: int, hip_stream: int = 0) -> None:
+    """hops: one dict per hop with the raw device addresses nbr, eid, ts, count, rowptr, cmp_nbr, cmp_eid, cmp_ts."""
+    vp = lambda x: C.c_void_p(x or None)
+    fo = (C.c_int32 * len(fanouts))(*fanouts)
+    hb = (tns_hop_buffers * len(hops))()
+    for i, h in enumerate(hops):
+        for name, _ in tns_hop_buffers._fields_:
+            setattr(hb[i], name, h[name] or None)
+    _check(lib().tns_run_khop(plan, len(fanouts), fo, delta, Q, vp(d_targets), vp(d_t_start), vp(d_t_end),
+                              vp(d_inst_rowptr), query_id_base, hb, vp(d_workspace), workspace_bytes, vp(hip_stream)),
+           "tns_run_khop")
+
+
 def tns_compact(plan, Q: int, d_out_nbr: int, d_out_eid: int, d_out_ts: int, d_out_count: int, d_rowptr: int,
                 d_cmp_nbr: int, d_cmp_eid: int, d_cmp_ts: int, d_workspace: int, workspace_bytes: int,
                 hip_stream: int = 0) -> None:
@@ -198,6 +228,7 @@ class Plan:
                  num_instances: int = 1, sizing: int = TNS_SIZING_ADAPTIVE, inclusive_end: int = 0, seed: int = 0,
                  device: int = 0, flags: int = 0):
         self.num_nodes, self.fanout, self.num_instances, self.device = num_nodes, fanout, num_instances, device
+        self.policy = policy
         self._h = tns_plan_create(num_nodes, fanout, policy, block_threshold, num_instances, sizing, inclusive_end,
                                   seed, device, flags)
 
@@ -207,7 +238,7 @@ class Plan:
 
     def set_sampler(self, fanout: int, policy: int = TNS_POLICY_RECENT, inclusive_end: int = 0, seed: int = 0):
         tns_set_sampler(self._h, fanout, policy, inclusive_end, seed)
-        self.fanout = fanout
+        self.fanout, self.policy = fanout, policy
 
     def add_edges(self, src, dst, ts, eid=None, instance: int = 0):
         tns_add_edges(self._h, instance, src, dst, ts, eid)
@@ -259,6 +290,32 @@ class Plan:
                     p(out.get("rowptr")), p(out.get("cmp_nbr")), p(out.get("cmp_eid")), p(out.get("cmp_ts")),
                     p(out.get("workspace")), 0 if out.get("workspace") is None else out["workspace"].numel(), stream)
         return out
+
+    def run_khop(self, fanouts, targets, t_start, t_end, inst_rowptr=None, delta: float = float("inf"),
+                 query_id_base: int = 0):
+        """Multi-hop sampling; returns one dict of output tensors per hop (sized for the most
+        queries the hop can have) plus the workspace tensor."""
+        import torch
+        dev = torch.device("cuda", self.device)
+        Q = int(targets.shape[0])
+        hops, cap = [], Q
+        for f in fanouts:
+            hops.append(dict(nbr=torch.empty(cap * f, dtype=torch.int32, device=dev),
+                             eid=torch.empty(cap * f, dtype=torch.int32, device=dev),
+                             ts=torch.empty(cap * f, dtype=torch.float32, device=dev),
+                             count=torch.empty(cap, dtype=torch.int32, device=dev),
+                             rowptr=torch.empty(cap + 1, dtype=torch.int64, device=dev),
+                             cmp_nbr=torch.empty(cap * f, dtype=torch.int32, device=dev),
+                             cmp_eid=torch.empty(cap * f, dtype=torch.int32, device=dev),
+                             cmp_ts=torch.empty(cap * f, dtype=torch.float32, device=dev), cap=cap, fanout=f))
+            cap *= f
+        ws = torch.empty(tns_workspace_khop(self._h, fanouts, Q), dtype=torch.uint8, device=dev)
+        p = lambda t: 0 if t is None else t.data_ptr()
+        ptrs = [{k: p(v) for k, v in h.items() if k not in ("cap", "fanout")} for h in hops]
+        with torch.cuda.device(self.device):
+            tns_run_khop(self._h, list(fanouts), delta, Q, p(targets), p(t_start), p(t_end), p(inst_rowptr),
+                         query_id_base, ptrs, ws.data_ptr(), ws.numel(), torch.cuda.current_stream().cuda_stream)
+        return hops, ws
 
     def close(self):
         if getattr(self, "_h", None):

@@ -1,6 +1,7 @@
 // C ABI of the library (include/tns.h): plan lifetime, ingestion, commit, run, statistics.
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -212,6 +213,7 @@ static int fill_sample_args(tns_plan* plan, int64_t Q, const int32_t* d_targets,
     if (plan->cfg.num_instances > 1 && !d_inst_rowptr) return fail(TNS_EINVAL, "d_inst_rowptr is required with several instances");
     if (Q > (int64_t(1) << 36)) return fail(TNS_ESIZE, "more than 2^36 queries in one call: split the batch");
     a = tns::SampleArgs{};
+    a.delta = INFINITY;
     a.nodes = plan->d_nodes.ptr;
     a.dir = plan->d_dir.ptr;
     a.edges = reinterpret_cast<const uint32_t*>(plan->d_edges.ptr);
@@ -275,7 +277,12 @@ int tns_run(tns_plan* plan, int64_t Q, const int32_t* d_targets, const float* d_
     a.out_eid = d_out_eid;
     a.out_ts = d_out_ts;
     a.out_count = d_out_count;
-    if (want_cmp) {   // one pass: sampling with the padding removal fused in
+    // Recent policy: one pass, sampling with the padding removal fused in.  Uniform policy: the
+    // walk lengths differ much more between tiles, which makes the fused kernel's chained scan
+    // wait longer than a second pass over the padded rows costs (measured on C5: 48 ms fused,
+    // 42 ms in two steps), so the two steps are kept apart there.
+    const bool fuse = want_cmp && plan->cfg.policy == TNS_POLICY_RECENT;
+    if (fuse) {
         a.scan_ws = d_workspace;
         a.rowptr = d_rowptr;
         a.cmp_nbr = d_cmp_nbr;
@@ -284,6 +291,121 @@ int tns_run(tns_plan* plan, int64_t Q, const int32_t* d_targets, const float* d_
     }
     const hipError_t e = tns::launch_sample(a, stream);
     if (e != hipSuccess) return fail_hip(e, "launching the sampling kernel");
+    if (want_cmp && !fuse)
+        return run_compact(plan, Q, d_out_nbr, d_out_eid, d_out_ts, d_out_count, d_rowptr, d_cmp_nbr, d_cmp_eid,
+                           d_cmp_ts, d_workspace, stream);
+    return TNS_OK;
+}
+
+namespace {
+constexpr int kMaxHops = 8;
+// caps[h] = most queries hop h can have; false if the sizes leave the supported range
+bool khop_caps(int32_t num_hops, const int32_t* fanouts, int64_t Q, int64_t* caps) {
+    int64_t cap = Q;
+    for (int h = 0; h < num_hops; ++h) {
+        if (fanouts[h] < 1 || fanouts[h] > TNS_MAX_FANOUT) return false;
+        caps[h] = cap;
+        if (cap > (int64_t(1) << 36) / fanouts[h]) return false;
+        cap *= fanouts[h];
+    }
+    return true;
+}
+size_t khop_header_bytes(int32_t num_hops, int32_t num_instances) {
+    // per hop: the dense total (next hop's query count) and the instance offsets of the next hop
+    const size_t per_hop = (size_t)(num_instances + 2) * sizeof(int64_t);
+    return ((size_t)num_hops * per_hop + 255) & ~size_t(255);
+}
+}  // namespace
+
+int tns_workspace_khop(const tns_plan* plan, int32_t num_hops, const int32_t* fanouts, int64_t Q, size_t* bytes) {
+    g_err.clear();
+    if (!plan || !fanouts || !bytes || Q < 0) return fail(TNS_EINVAL, "null pointer or negative Q");
+    if (num_hops < 1 || num_hops > kMaxHops) return fail(TNS_EINVAL, "num_hops must be in [1, 8]");
+    int64_t caps[kMaxHops];
+    if (!khop_caps(num_hops, fanouts, Q, caps)) return fail(TNS_ESIZE, "fan-out out of range or more than 2^36 queries in a hop");
+    size_t scan = 0;
+    for (int h = 0; h < num_hops; ++h) scan = std::max(scan, tns::compact_workspace_bytes(caps[h]));
+    *bytes = khop_header_bytes(num_hops, plan->cfg.num_instances) + scan;
+    return TNS_OK;
+}
+
+int tns_run_khop(tns_plan* plan, int32_t num_hops, const int32_t* fanouts, float delta, int64_t Q,
+                 const int32_t* d_targets, const float* d_t_start, const float* d_t_end, const int64_t* d_inst_rowptr,
+                 int64_t query_id_base, const tns_hop_buffers* hops, void* d_workspace, size_t workspace_bytes,
+                 void* hip_stream) {
+    g_err.clear();
+    if (!plan || !fanouts || !hops) return fail(TNS_EINVAL, "null plan, fanouts or hops");
+    if (num_hops < 1 || num_hops > kMaxHops) return fail(TNS_EINVAL, "num_hops must be in [1, 8]");
+    if (std::isnan(delta) || delta < 0) return fail(TNS_EINVAL, "delta must be >= 0 (or +infinity)");
+    int64_t caps[kMaxHops];
+    if (Q < 0 || !khop_caps(num_hops, fanouts, Q, caps)) return fail(TNS_ESIZE, "fan-out out of range or more than 2^36 queries in a hop");
+    size_t need = 0;
+    int rc = tns_workspace_khop(plan, num_hops, fanouts, Q, &need);
+    if (rc) return rc;
+    if (!d_workspace) return fail(TNS_EINVAL, "null workspace");
+    if (workspace_bytes < need) return fail(TNS_ESIZE, "workspace smaller than tns_workspace_khop()");
+    if (reinterpret_cast<uintptr_t>(d_workspace) & 255) return fail(TNS_EINVAL, "workspace must be 256-byte aligned");
+    for (int h = 0; h < num_hops; ++h) {
+        const tns_hop_buffers& b = hops[h];
+        if (!b.rowptr || (caps[h] > 0 && (!b.nbr || !b.eid || !b.ts || !b.count || !b.cmp_nbr || !b.cmp_eid || !b.cmp_ts)))
+            return fail(TNS_EINVAL, "null buffer in hops[]");
+    }
+    tns::SampleArgs a;
+    if ((rc = fill_sample_args(plan, Q, d_targets, d_t_start, d_t_end, d_inst_rowptr, query_id_base, a))) return rc;
+
+    DeviceGuard guard(plan->cfg.device);
+    if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the plan's device");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int32_t I = plan->cfg.num_instances;
+    int64_t* header = static_cast<int64_t*>(d_workspace);
+    void* scan_ws = static_cast<unsigned char*>(d_workspace) + khop_header_bytes(num_hops, I);
+    const bool fuse = plan->cfg.policy == TNS_POLICY_RECENT;
+
+    for (int h = 0; h < num_hops; ++h) {
+        const tns_hop_buffers& b = hops[h];
+        int64_t* total = header + (size_t)h * (I + 2);          // dense total of hop h = query count of hop h+1
+        int64_t* next_inst = total + 1;                         // [I + 1]
+        a.fanout = fanouts[h];
+        a.Q = caps[h];
+        a.out_nbr = b.nbr;
+        a.out_eid = b.eid;
+        a.out_ts = b.ts;
+        a.out_count = b.count;
+        a.total_out = total;
+        a.scan_ws = nullptr;
+        if (fuse) {
+            a.scan_ws = scan_ws;
+            a.rowptr = b.rowptr;
+            a.cmp_nbr = b.cmp_nbr;
+            a.cmp_eid = b.cmp_eid;
+            a.cmp_ts = b.cmp_ts;
+        }
+        hipError_t e = tns::launch_sample(a, stream);
+        if (e != hipSuccess) return fail_hip(e, "launching the sampling kernel of a hop");
+        if (!fuse) {
+            tns::CompactArgs c{};
+            c.nbr = b.nbr; c.eid = b.eid; c.ts = b.ts; c.count = b.count;
+            c.rowptr = b.rowptr; c.cmp_nbr = b.cmp_nbr; c.cmp_eid = b.cmp_eid; c.cmp_ts = b.cmp_ts;
+            c.Q = caps[h]; c.Q_dev = a.Q_dev; c.total_out = total;
+            c.fanout = fanouts[h];
+            c.workspace = scan_ws;
+            e = tns::launch_compact(c, stream);
+            if (e != hipSuccess) return fail_hip(e, "launching the compaction kernels of a hop");
+        }
+        if (h + 1 == num_hops) break;
+        // queries of the next hop: the dense entries of this one
+        if (a.inst_rowptr) {
+            e = tns::launch_hop_inst_rowptr(a.inst_rowptr, b.rowptr, I, next_inst, stream);
+            if (e != hipSuccess) return fail_hip(e, "launching the instance-offset kernel");
+            a.inst_rowptr = next_inst;
+        }
+        a.targets = b.cmp_nbr;
+        a.t_end = b.cmp_ts;
+        a.t_start = nullptr;
+        a.delta = delta;
+        a.Q_dev = total;
+        a.qid_base += caps[h];
+    }
     return TNS_OK;
 }
 

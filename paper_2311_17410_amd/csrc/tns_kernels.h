@@ -34,7 +34,10 @@ struct SampleArgs {
     int32_t* cmp_nbr;
     int32_t* cmp_eid;
     float* cmp_ts;
-    int64_t Q;
+    int64_t Q;               // number of queries, or an upper bound of it when Q_dev is set
+    const int64_t* Q_dev;    // may be null; device-resident number of queries (hops after the first)
+    int64_t* total_out;      // may be null; fused variant: also receives the dense total (rowptr[Q])
+    float delta;             // window length used when t_start is null: t_start = t_end - delta (+inf: unbounded)
     int64_t num_nodes;
     int64_t num_dir;     // records in the directory pool (walks never index past it)
     int64_t qid_base;
@@ -57,6 +60,8 @@ struct CompactArgs {
     int32_t* cmp_eid;
     float* cmp_ts;
     int64_t Q;
+    const int64_t* Q_dev;    // may be null; device-resident number of queries
+    int64_t* total_out;      // may be null; also receives the dense total
     int32_t fanout;
     void* workspace;
 };
@@ -68,5 +73,7 @@ size_t compact_workspace_bytes(int64_t Q);
 // Both only enqueue kernels on `stream`; they return the first launch error.
 hipError_t launch_sample(const SampleArgs& a, hipStream_t stream);
 hipError_t launch_compact(const CompactArgs& a, hipStream_t stream);
+hipError_t launch_hop_inst_rowptr(const int64_t* cur, const int64_t* rowptr, int32_t num_instances, int64_t* next,
+                                  hipStream_t stream);
 
 }  // namespace tns

@@ -102,12 +102,17 @@ __device__ __forceinline__ int64_t lookback_exclusive(ScanWorkspace* ws, int64_t
 
 // Clears the ticket, the error flag and the tile states before a fused launch (a kernel rather
 // than a memset, so that the launch sequence can be captured into a graph).
-__global__ void __launch_bounds__(256) tns_scan_init(ScanWorkspace* ws, int64_t num_tiles, int64_t* rowptr0, int64_t Q) {
+__global__ void __launch_bounds__(256) tns_scan_init(ScanWorkspace* ws, int64_t num_tiles, int64_t* rowptr0, int64_t Q,
+                                                     const int64_t* Q_dev, int64_t* total_out) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i == 0) {
         ws->ticket = 0;
         ws->error = 0;
-        if (Q == 0) rowptr0[0] = 0;
+        if (Q_dev && *Q_dev < Q) Q = *Q_dev;
+        if (Q <= 0) {          // no query will write the end of rowptr
+            rowptr0[0] = 0;
+            if (total_out) *total_out = 0;
+        }
     }
     if (i < num_tiles) ws->status[i] = 0;
 }
@@ -230,16 +235,18 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
     const int64_t q0 = (tile * waves_per_wg + wave) * kWave;
     const int64_t q = q0 + lane;
     const int32_t f = p.fanout;
+    // number of queries: the host's bound, or fewer when the count lives on the device (later hops)
+    const int64_t Q = p.Q_dev ? min(p.Q, *p.Q_dev) : p.Q;
 
     Walk<POLICY, INCL, pos_t> w;
     w.f = f;
     w.s_pos = reinterpret_cast<pos_t*>(smem) + (size_t)wave * kWave * stride + (size_t)lane * stride;
     w.edges = p.edges;
     int32_t n_nodes = 0;
-    if (q < p.Q) {
+    if (q < Q) {
         const int32_t v = p.targets[q];
         w.te = p.t_end[q];
-        w.tb = p.t_start ? p.t_start[q] : -INFINITY;
+        w.tb = p.t_start ? p.t_start[q] : (p.delta == INFINITY ? -INFINITY : w.te - p.delta);
         int64_t nbase = 0;
         bool ok = (uint32_t)v < (uint64_t)p.num_nodes && !(w.te != w.te) && !(w.tb != w.tb);
         if (p.inst_rowptr) {
@@ -340,9 +347,12 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
         // one loop that gathers and writes both the padded row and the dense copy; needs the tile offset
         auto gather_both = [&]() {
             const int64_t row = s_tile_base + wave_off + (inc - k);
-            if (q < p.Q) {
+            if (q < Q) {
                 p.rowptr[q] = row;
-                if (q == p.Q - 1) p.rowptr[p.Q] = row + k;
+                if (q == Q - 1) {
+                    p.rowptr[Q] = row + k;
+                    if (p.total_out) *p.total_out = row + k;
+                }
             }
             for (int32_t it = 0; it < f; ++it) {
                 const uint32_t s = (uint32_t)(it * kWave + lane);
@@ -350,7 +360,7 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
                 const int32_t j = (int32_t)(s - ql * (uint32_t)f);
                 const int32_t kq = __shfl(k, (int)ql, kWave);
                 const int64_t rowq = __shfl(row, (int)ql, kWave);
-                if (q0 + (int64_t)ql < p.Q) {
+                if (q0 + (int64_t)ql < Q) {
                     int32_t nbr = -1, eid = -1;
                     float t = 0.0f;
                     if (j < kq) {
@@ -387,7 +397,7 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
                         const Edge e = *reinterpret_cast<const Edge*>(p.edges + pos);
                         vn[it] = e.nbr; ve[it] = e.eid; vt[it] = e.ts;
                     }
-                    if (q0 + (int64_t)ql < p.Q) {
+                    if (q0 + (int64_t)ql < Q) {
                         p.out_nbr[out0 + s] = vn[it];
                         p.out_eid[out0 + s] = ve[it];
                         p.out_ts[out0 + s] = vt[it];
@@ -396,9 +406,12 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
             }
             __syncthreads();
             const int64_t row = s_tile_base + wave_off + (inc - k);
-            if (q < p.Q) {
+            if (q < Q) {
                 p.rowptr[q] = row;
-                if (q == p.Q - 1) p.rowptr[p.Q] = row + k;
+                if (q == Q - 1) {
+                    p.rowptr[Q] = row + k;
+                    if (p.total_out) *p.total_out = row + k;
+                }
             }
 #pragma unroll
             for (int it = 0; it < kFusedRegSlots; ++it) {
@@ -429,7 +442,7 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
             const uint32_t ql = div_by(s, (uint32_t)f, f_magic);
             const int32_t j = (int32_t)(s - ql * (uint32_t)f);
             const int32_t kq = __shfl(k, (int)ql, kWave);
-            if (q0 + (int64_t)ql < p.Q) {
+            if (q0 + (int64_t)ql < Q) {
                 int32_t nbr = -1, eid = -1;
                 float t = 0.0f;
                 if (j < kq) {
@@ -443,15 +456,17 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
             }
         }
     }
-    if (q < p.Q) p.out_count[q] = k;
+    if (q < Q) p.out_count[q] = k;
 }
 
 // ---- padding removal -------------------------------------------------------------------
 
 // sum of counts per tile of kCompactTile queries
 __global__ void __launch_bounds__(256) tns_count_tile_sums(const int32_t* __restrict__ count, int64_t Q,
+                                                           const int64_t* __restrict__ Q_dev,
                                                            int32_t* __restrict__ tile_sums) {
     __shared__ int32_t s_w[4];
+    if (Q_dev) Q = min(Q, *Q_dev);
     const int64_t base = (int64_t)blockIdx.x * kCompactTile;
     int32_t v = 0;
 #pragma unroll
@@ -468,7 +483,9 @@ __global__ void __launch_bounds__(256) tns_count_tile_sums(const int32_t* __rest
 
 // exclusive scan of the tile sums (int64), one workgroup; also writes rowptr[Q]
 __global__ void __launch_bounds__(1024) tns_scan_tile_sums(const int32_t* __restrict__ tile_sums, int64_t num_tiles,
-                                                           int64_t* __restrict__ tile_offs, int64_t* __restrict__ total) {
+                                                           int64_t* __restrict__ tile_offs, int64_t* __restrict__ rowptr,
+                                                           int64_t Q, const int64_t* __restrict__ Q_dev,
+                                                           int64_t* __restrict__ total_out) {
     __shared__ int32_t s_w[16];
     __shared__ int64_t s_carry;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -493,7 +510,11 @@ __global__ void __launch_bounds__(1024) tns_scan_tile_sums(const int32_t* __rest
         if (threadIdx.x == 0) s_carry = carry + all;
         __syncthreads();
     }
-    if (threadIdx.x == 0) *total = s_carry;
+    if (threadIdx.x == 0) {
+        if (Q_dev) Q = min(Q, *Q_dev);
+        rowptr[Q < 0 ? 0 : Q] = s_carry;          // end of rowptr for the actual number of queries
+        if (total_out) *total_out = s_carry;
+    }
 }
 
 // rowptr of the tile's queries and scatter of the filled slots to the dense arrays
@@ -503,6 +524,7 @@ __global__ void __launch_bounds__(256) tns_compact_scatter(const CompactArgs a, 
     __shared__ int32_t s_cnt[kCompactTile];
     __shared__ int32_t s_w[4];
     constexpr int kPer = kCompactTile / 256;
+    const int64_t Q = a.Q_dev ? min(a.Q, *a.Q_dev) : a.Q;
     const int64_t base = (int64_t)blockIdx.x * kCompactTile;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int32_t c[kPer];
@@ -510,7 +532,7 @@ __global__ void __launch_bounds__(256) tns_compact_scatter(const CompactArgs a, 
 #pragma unroll
     for (int i = 0; i < kPer; ++i) {
         const int64_t q = base + threadIdx.x * kPer + i;
-        c[i] = q < a.Q ? a.count[q] : 0;
+        c[i] = q < Q ? a.count[q] : 0;
         sum += c[i];
     }
     const int32_t inc = wave_inclusive_scan(sum, lane);
@@ -524,7 +546,7 @@ __global__ void __launch_bounds__(256) tns_compact_scatter(const CompactArgs a, 
         const int ql = threadIdx.x * kPer + i;
         s_excl[ql] = excl;
         s_cnt[ql] = c[i];
-        if (base + ql < a.Q) a.rowptr[base + ql] = tile_off + excl;
+        if (base + ql < Q) a.rowptr[base + ql] = tile_off + excl;
         excl += c[i];
     }
     __syncthreads();
@@ -532,7 +554,7 @@ __global__ void __launch_bounds__(256) tns_compact_scatter(const CompactArgs a, 
     const uint32_t f = (uint32_t)a.fanout;
     const uint32_t slots = kCompactTile * f;
     const int64_t in0 = base * f;
-    const int64_t in_end = a.Q * (int64_t)f;
+    const int64_t in_end = Q * (int64_t)f;
     for (uint32_t s = threadIdx.x; s < slots; s += 256) {
         if (in0 + s >= in_end) break;
         const uint32_t ql = div_by(s, f, f_magic);
@@ -544,6 +566,14 @@ __global__ void __launch_bounds__(256) tns_compact_scatter(const CompactArgs a, 
             a.cmp_ts[d] = a.ts[in0 + s];
         }
     }
+}
+
+// Next hop's instance offsets: instance b's queries of the next hop are the dense entries of its
+// queries of this hop, so next[b] = rowptr[cur[b]] (cur[I] = number of queries of this hop).
+__global__ void __launch_bounds__(256) tns_hop_inst_rowptr(const int64_t* __restrict__ cur, const int64_t* __restrict__ rowptr,
+                                                           int32_t num_instances, int64_t* __restrict__ next) {
+    const int b = blockIdx.x * 256 + threadIdx.x;
+    if (b <= num_instances) next[b] = rowptr[cur[b]];
 }
 
 inline uint32_t magic_for(int32_t f) { return f <= 1 ? 0u : (uint32_t)(((uint64_t(1) << 32) + (uint64_t)f - 1) / (uint64_t)f); }
@@ -561,7 +591,7 @@ hipError_t launch_sample_t(const SampleArgs& a, hipStream_t stream) {
     if (FUSED) {
         const unsigned init_grid = (unsigned)std::max<int64_t>(1, (grid + 255) / 256);
         hipLaunchKernelGGL(tns_scan_init, dim3(init_grid), dim3(256), 0, stream, static_cast<ScanWorkspace*>(a.scan_ws),
-                           grid, a.rowptr, a.Q);
+                           grid, a.rowptr, a.Q, a.Q_dev, a.total_out);
     }
     if (grid <= 0) return hipGetLastError();
     const size_t lds = per_wave * waves;
@@ -596,6 +626,13 @@ hipError_t launch_sample(const SampleArgs& a, hipStream_t stream) {
 #undef TNS_DISPATCH
 }
 
+hipError_t launch_hop_inst_rowptr(const int64_t* cur, const int64_t* rowptr, int32_t num_instances, int64_t* next,
+                                  hipStream_t stream) {
+    hipLaunchKernelGGL(tns_hop_inst_rowptr, dim3((unsigned)(num_instances / 256 + 1)), dim3(256), 0, stream, cur, rowptr,
+                       num_instances, next);
+    return hipGetLastError();
+}
+
 hipError_t launch_compact(const CompactArgs& a, hipStream_t stream) {
     const int64_t tiles = (a.Q + kCompactTile - 1) / kCompactTile;
     unsigned char* ws = static_cast<unsigned char*>(a.workspace);
@@ -604,9 +641,10 @@ hipError_t launch_compact(const CompactArgs& a, hipStream_t stream) {
     int64_t* offs = reinterpret_cast<int64_t*>(ws + sums_bytes);
     if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
     if (tiles > 0) {
-        hipLaunchKernelGGL(tns_count_tile_sums, dim3((unsigned)tiles), dim3(256), 0, stream, a.count, a.Q, sums);
+        hipLaunchKernelGGL(tns_count_tile_sums, dim3((unsigned)tiles), dim3(256), 0, stream, a.count, a.Q, a.Q_dev, sums);
     }
-    hipLaunchKernelGGL(tns_scan_tile_sums, dim3(1), dim3(1024), 0, stream, sums, tiles, offs, a.rowptr + a.Q);
+    hipLaunchKernelGGL(tns_scan_tile_sums, dim3(1), dim3(1024), 0, stream, sums, tiles, offs, a.rowptr, a.Q, a.Q_dev,
+                       a.total_out);
     if (tiles > 0) {
         hipLaunchKernelGGL(tns_compact_scatter, dim3((unsigned)tiles), dim3(256), 0, stream, a, offs,
                            magic_for(a.fanout));

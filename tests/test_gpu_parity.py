@@ -161,6 +161,78 @@ def test_standalone_compaction_equals_fused(B, oracle_lib):
     plan.close()
 
 
+# ---- multi-hop --------------------------------------------------------------------------------
+
+def oracle_khop(oracle, wl, targets, t_start, t_end, inst_rowptr, fanouts, delta, policy, seed, base=0):
+    """Hop h+1 takes the dense result of hop h as its queries: target = sampled neighbour, window
+    end = sampled edge's time, start = end - delta (fp32).  Returns per hop (padded result, rowptr,
+    number of queries)."""
+    out, cap = [], len(targets)
+    for f in fanouts:
+        ref = oracle_sample(oracle, wl, targets, t_start, t_end, inst_rowptr, f, policy, 0, seed, query_id_base=base)
+        rowptr, cn, ce, ct = oracle.compact(ref)
+        out.append((ref, rowptr, cn, ce, ct))
+        if inst_rowptr is not None:
+            inst_rowptr = rowptr[inst_rowptr]
+        targets, t_end = cn, ct
+        t_start = None if np.isinf(delta) else (ct - np.float32(delta)).astype(np.float32)
+        base += cap
+        cap *= f
+    return out
+
+
+@pytest.mark.parametrize("policy", [0, 1])
+@pytest.mark.parametrize("fanouts,delta", [([10, 10], float("inf")), ([3, 2, 4], 40.0), ([1, 1, 1, 1], float("inf"))])
+def test_khop_matches_chained_oracle(B, oracle_lib, policy, fanouts, delta):
+    import torch
+    st = W.tiny_stream(91, 4000, 37, 256, ties=True)
+    wl = wl_of(st, fanout=fanouts[0])
+    plan = build_plan(B, wl, policy, 0, seed=9)
+    targets, t_start, t_end = W.random_queries(92, st, 700 + 5)
+    dev = torch.device("cuda", 0)
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    hops, ws = plan.run_khop(fanouts, d(targets), d(t_start), d(t_end), delta=delta, query_id_base=1000)
+    torch.cuda.synchronize()
+    ref = oracle_khop(oracle_lib, wl, targets, t_start, t_end, None, fanouts, delta, policy, 9, base=1000)
+    n = len(targets)
+    for h, (r, rowptr, cn, ce, ct) in enumerate(ref):
+        f = fanouts[h]
+        g = hops[h]
+        assert np.array_equal(g["count"][:n].cpu().numpy(), r.count), f"hop {h} count"
+        assert np.array_equal(g["eid"][:n * f].cpu().numpy().reshape(n, f), r.eid), f"hop {h} eid"
+        assert np.array_equal(g["nbr"][:n * f].cpu().numpy().reshape(n, f), r.nbr), f"hop {h} nbr"
+        assert np.array_equal(g["ts"][:n * f].cpu().numpy().reshape(n, f).view(np.int32), r.ts.view(np.int32)), f"hop {h} ts"
+        assert np.array_equal(g["rowptr"][:n + 1].cpu().numpy(), rowptr), f"hop {h} rowptr"
+        tot = int(rowptr[-1])
+        assert np.array_equal(g["cmp_eid"][:tot].cpu().numpy(), ce) and np.array_equal(g["cmp_nbr"][:tot].cpu().numpy(), cn)
+        assert np.array_equal(g["cmp_ts"][:tot].cpu().numpy().view(np.int32), ct.view(np.int32))
+        n = tot
+    plan.close()
+
+
+def test_khop_batched_instances_and_c2(B, oracle_lib):
+    import torch
+    dev = torch.device("cuda", 0)
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    for wl in (W.c4(instances=8, log2_n=12), W.c2()):
+        targets, t_start, t_end, rowptr = wl.queries()
+        rp = rowptr if wl.num_instances > 1 else None
+        plan = build_plan(B, wl, 0, 0)
+        fanouts = [10, 10] if wl.num_instances > 1 else [10, 5]
+        hops, ws = plan.run_khop(fanouts, d(targets), None, d(t_end), None if rp is None else d(rp))
+        torch.cuda.synchronize()
+        ref = oracle_khop(oracle_lib, wl, targets, None, t_end, rp, fanouts, float("inf"), 0, 0)
+        n = len(targets)
+        for h, (r, rowptr_h, cn, ce, ct) in enumerate(ref):
+            f = fanouts[h]
+            assert np.array_equal(hops[h]["count"][:n].cpu().numpy(), r.count), (wl.name, h)
+            assert np.array_equal(hops[h]["eid"][:n * f].cpu().numpy().reshape(n, f), r.eid), (wl.name, h)
+            assert np.array_equal(hops[h]["rowptr"][:n + 1].cpu().numpy(), rowptr_h), (wl.name, h)
+            n = int(rowptr_h[-1])
+            assert np.array_equal(hops[h]["cmp_eid"][:n].cpu().numpy(), ce), (wl.name, h)
+        plan.close()
+
+
 # ---- the configurations --------------------------------------------------------------------
 
 def _check_config(B, oracle, wl, threads=16, window=True, policies=(0, 1)):

@@ -14,6 +14,7 @@
 
 #include <algorithm>
 #include <cstdlib>
+#include <cstdlib>
 
 namespace tns {
 namespace {
@@ -61,6 +62,7 @@ __device__ __forceinline__ int32_t wave_inclusive_scan(int32_t v, int lane) {
 // already started; the wait is bounded and sets the error flag if the bound is ever hit.
 constexpr uint64_t kStTotal = 1ull << 62, kStPrefix = 2ull << 62, kStMask = 3ull << 62;
 constexpr int kSpinLimit = 1 << 22;
+constexpr int kCoopGroup = 16;        // lanes per query in the cooperative search (recent policy, fan-out <= 16)
 constexpr int kFusedRegSlots = 10;   // fan-outs up to this keep the gathered edges in registers (fused variant)
 
 struct ScanWorkspace {
@@ -129,6 +131,13 @@ struct Walk {
     int64_t c = 0;                // uniform: candidates seen in all overlapping blocks
     int32_t t_first = -1, t_last = -1, hi_first = 0, lo_last = 0;   // uniform: first/last overlapping block
     int32_t n_blocks = 0, n_probes = 0;                              // counted for the byte model
+    // recent: search left to the wave.  When the window end falls inside a block, the lane only
+    // narrows the search to at most `group` slots [d_lo, d_lo + d_n) of that block (edges before
+    // d_lo are known to qualify); the wave then reads those timestamps side by side and counts,
+    // right before it gathers from the same lines.
+    int32_t group = 0;            // 0: the lane does every search itself
+    int64_t d_off = -1;           // slot index of that block's first edge, -1: nothing left to the wave
+    int32_t d_lo = 0, d_n = 0;
 
     // first index i in [0, n) with ts[i] >= x (STRICT=false) or ts[i] > x (STRICT=true)
     template <bool STRICT>
@@ -154,6 +163,20 @@ struct Walk {
         // candidate range [lo, hi) of the block; t_min / t_max settle most cases without a search
         int32_t hi = size;
         const bool all_before_end = INCL ? (te >= r.t_max) : (te > r.t_max);
+        if (POLICY == 0 && group > 0 && !all_before_end && !(tb > r.t_min)) {
+            // only the newest overlapping block can contain the window end, so nothing is recorded yet
+            int32_t lo = 0;
+            while (hi - lo > group) {
+                const int32_t mid = lo + ((hi - lo) >> 1);
+                const float tm = __uint_as_float(edges[slot_word(off + mid)]);
+                ++n_probes;
+                const bool ge = INCL ? (tm > te) : (tm >= te);
+                if (ge) hi = mid; else lo = mid + 1;
+            }
+            d_off = off; d_lo = lo; d_n = hi - lo;
+            n_probes += d_n;
+            return true;            // older blocks supply the remaining slots
+        }
         if (!all_before_end) hi = first_not_before<INCL>(off, size, te);
         int32_t lo = 0;
         if (tb > r.t_min) lo = first_not_before<false>(off, hi, tb);
@@ -200,6 +223,28 @@ struct Walk {
     }
 };
 
+// Ordering between LDS writes and reads of the SAME wave (rows are wave-private): the hardware
+// executes a wave's LDS operations in order, so only the compiler must not reorder them.
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+__device__ __forceinline__ int64_t shfl64(int64_t v, int src) {
+    const int lo = __shfl((int)(uint32_t)(v & 0xffffffffll), src, kWave);
+    const int hi = __shfl((int)(v >> 32), src, kWave);
+    return ((int64_t)hi << 32) | (uint32_t)lo;
+}
+
+// Word index of the edge in slot j of a query: the first hq slots come from the block whose
+// search the wave finished (newest first), the others from the positions the lane recorded.
+template <typename pos_t>
+__device__ __forceinline__ int64_t slot_position(const pos_t* __restrict__ w_pos, int32_t stride, uint32_t ql, int32_t j,
+                                                 int32_t hq, int64_t dq) {
+    if (j < hq) return slot_word(dq + hq - 1 - j);
+    return (int64_t)w_pos[ql * stride + (j - hq)];
+}
+
 __device__ __forceinline__ BlockRec as_rec(const uint4& u) {
     BlockRec r;
     r.t_min = __uint_as_float(u.x);
@@ -213,7 +258,7 @@ __device__ __forceinline__ BlockRec as_rec(const uint4& u) {
 // offsets obtained from a chained scan over the workgroups.
 template <int POLICY, bool INCL, typename pos_t, bool COUNT, bool FUSED>
 __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const SampleArgs p, const int32_t stride,
-                                                         const uint32_t f_magic) {
+                                                                          const uint32_t f_magic, const int32_t gshift) {
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int64_t s_tile_base;
     __shared__ int32_t s_wave_sum[16];
@@ -242,6 +287,9 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
     w.f = f;
     w.s_pos = reinterpret_cast<pos_t*>(smem) + (size_t)wave * kWave * stride + (size_t)lane * stride;
     w.edges = p.edges;
+    w.group = (POLICY == 0 && gshift >= 0) ? (1 << gshift) : 0;
+    w.te = 0.0f;
+    w.tb = 0.0f;
     int32_t n_nodes = 0;
     if (q < Q) {
         const int32_t v = p.targets[q];
@@ -306,7 +354,44 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
             }
         }
     }
-    const int32_t k = w.k;
+    // Recent policy, stage 1 of the cooperative part: finish the searches the lanes left open.
+    // A group of 16 lanes serves one query: lane j of the group reads the timestamp of slot j of
+    // the query's search window; the number of qualifying slots comes from a ballot.  All loads are
+    // issued before the first result is used, so the wave pays the memory latency once.
+    int32_t h = 0;               // edges of the searched block that lie before the window end
+    if (POLICY == 0 && gshift >= 0) {
+        constexpr int G = kCoopGroup, groups = kWave / G;
+        unsigned char* extra = smem + (size_t)waves_per_wg * kWave * stride * sizeof(pos_t);
+        // per query: window start (40-bit slot index) with the window size in the upper bits,
+        // the window end time, and the result
+        uint2* s_q = reinterpret_cast<uint2*>(extra) + wave * kWave;
+        float* s_te = reinterpret_cast<float*>(extra + (size_t)waves_per_wg * kWave * sizeof(uint2)) + wave * kWave;
+        int32_t* s_h = reinterpret_cast<int32_t*>(extra + (size_t)waves_per_wg * kWave * (sizeof(uint2) + sizeof(float))) + wave * kWave;
+        const int64_t win0 = w.d_off + w.d_lo;
+        s_q[lane] = make_uint2((uint32_t)(win0 & 0xffffffffll), ((uint32_t)(win0 >> 32) & 0xffu) | ((uint32_t)w.d_n << 8));
+        s_te[lane] = w.te;
+        wave_lds_sync();
+        const int g = lane / G, j = lane % G;
+        float tj[G];
+#pragma unroll
+        for (int it = 0; it < G; ++it) {
+            const uint2 d = s_q[it * groups + g];
+            tj[it] = 0.0f;
+            if (j < (int32_t)(d.y >> 8)) tj[it] = __uint_as_float(p.edges[slot_word((((int64_t)(d.y & 0xffu)) << 32 | d.x) + j)]);
+        }
+#pragma unroll
+        for (int it = 0; it < G; ++it) {
+            const int32_t n = (int32_t)(s_q[it * groups + g].y >> 8);
+            const float teq = s_te[it * groups + g];
+            const bool qual = j < n && (INCL ? (tj[it] <= teq) : (tj[it] < teq));
+            const uint64_t m = __ballot(qual);
+            if (j == 0) s_h[it * groups + g] = __popcll((m >> (g * G)) & ((1ull << G) - 1));
+        }
+        wave_lds_sync();
+        if (w.d_off >= 0) h = w.d_lo + s_h[lane];
+    }
+    const int32_t k = POLICY == 0 ? min(f, h + w.k) : w.k;
+    const int64_t d_off = w.d_off;
     if (COUNT) {
         // totals of what this launch reads: node entries, block records, timestamp probes, edges
         unsigned long long v4[4] = {(unsigned long long)n_nodes, (unsigned long long)w.n_blocks,
@@ -334,9 +419,10 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
             if (i < wave) wave_off += t;
             wg_total += t;
         }
-        auto chain = [&]() {      // wave 0: publish the tile total, look back, publish the prefix
-            if (lane == 0 && tile > 0)
-                __hip_atomic_store(&ws->status[tile], kStTotal | (uint64_t)wg_total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // the tile total is published at once, so that later tiles can look past this one
+        if (wave == 0 && lane == 0 && tile > 0)
+            __hip_atomic_store(&ws->status[tile], kStTotal | (uint64_t)wg_total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        auto chain = [&]() {      // wave 0: look back for the tile's offset, publish the prefix
             const int64_t excl = tile > 0 ? lookback_exclusive(ws, tile, lane) : 0;
             if (lane == 0) {
                 __hip_atomic_store(&ws->status[tile], kStPrefix | (uint64_t)(excl + wg_total), __ATOMIC_RELAXED,
@@ -359,12 +445,14 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
                 const uint32_t ql = div_by(s, (uint32_t)f, f_magic);
                 const int32_t j = (int32_t)(s - ql * (uint32_t)f);
                 const int32_t kq = __shfl(k, (int)ql, kWave);
+                const int32_t hq = POLICY == 0 ? __shfl(h, (int)ql, kWave) : 0;
+                const int64_t dq = POLICY == 0 ? shfl64(d_off, (int)ql) : 0;
                 const int64_t rowq = __shfl(row, (int)ql, kWave);
                 if (q0 + (int64_t)ql < Q) {
                     int32_t nbr = -1, eid = -1;
                     float t = 0.0f;
                     if (j < kq) {
-                        const int64_t pos = (int64_t)w_pos[ql * stride + j];
+                        const int64_t pos = slot_position(w_pos, stride, ql, j, hq, dq);
                         const Edge e = *reinterpret_cast<const Edge*>(p.edges + pos);
                         nbr = e.nbr; eid = e.eid; t = e.ts;
                         p.cmp_nbr[rowq + j] = nbr;
@@ -378,10 +466,9 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
             }
         };
         if (f <= kFusedRegSlots) {
-            // While wave 0 resolves the tile offset, the other waves already gather and write
-            // their padded rows; the gathered edges stay in registers and only the dense copy
-            // waits for the offset.
-            if (wave == 0) chain();
+            // Every wave first gathers and writes its padded rows; the gathered edges stay in
+            // registers.  Wave 0 then looks back for the tile offset (the earlier tiles have had
+            // the time of a gather to publish their totals), and only the dense copy waits for it.
             int32_t vn[kFusedRegSlots], ve[kFusedRegSlots];
             float vt[kFusedRegSlots];
 #pragma unroll
@@ -392,8 +479,10 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
                     const uint32_t ql = div_by(s, (uint32_t)f, f_magic);
                     const int32_t j = (int32_t)(s - ql * (uint32_t)f);
                     const int32_t kq = __shfl(k, (int)ql, kWave);
+                    const int32_t hq = POLICY == 0 ? __shfl(h, (int)ql, kWave) : 0;
+                    const int64_t dq = POLICY == 0 ? shfl64(d_off, (int)ql) : 0;
                     if (j < kq) {
-                        const int64_t pos = (int64_t)w_pos[ql * stride + j];
+                        const int64_t pos = slot_position(w_pos, stride, ql, j, hq, dq);
                         const Edge e = *reinterpret_cast<const Edge*>(p.edges + pos);
                         vn[it] = e.nbr; ve[it] = e.eid; vt[it] = e.ts;
                     }
@@ -404,6 +493,7 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
                     }
                 }
             }
+            if (wave == 0) chain();
             __syncthreads();
             const int64_t row = s_tile_base + wave_off + (inc - k);
             if (q < Q) {
@@ -435,18 +525,20 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
             gather_both();
         }
     } else {
-        __syncthreads();
+        wave_lds_sync();
         // cooperative gather + padded write: the wave's 64*f slots in flat order
         for (int32_t it = 0; it < f; ++it) {
             const uint32_t s = (uint32_t)(it * kWave + lane);
             const uint32_t ql = div_by(s, (uint32_t)f, f_magic);
             const int32_t j = (int32_t)(s - ql * (uint32_t)f);
             const int32_t kq = __shfl(k, (int)ql, kWave);
+            const int32_t hq = POLICY == 0 ? __shfl(h, (int)ql, kWave) : 0;
+            const int64_t dq = POLICY == 0 ? shfl64(d_off, (int)ql) : 0;
             if (q0 + (int64_t)ql < Q) {
                 int32_t nbr = -1, eid = -1;
                 float t = 0.0f;
                 if (j < kq) {
-                    const int64_t pos = (int64_t)w_pos[ql * stride + j];
+                    const int64_t pos = slot_position(w_pos, stride, ql, j, hq, dq);
                     const Edge e = *reinterpret_cast<const Edge*>(p.edges + pos);
                     nbr = e.nbr; eid = e.eid; t = e.ts;
                 }
@@ -584,7 +676,12 @@ hipError_t launch_sample_t(const SampleArgs& a, hipStream_t stream) {
     const size_t per_wave = (size_t)kWave * stride * sizeof(pos_t);
     // The fused variant uses large workgroups: one chained-scan step per 1024 queries keeps the
     // rate at which tiles publish their totals low enough for the look-back to keep up.
-    int waves = (int)std::min<size_t>(FUSED ? 16 : 4, std::max<size_t>(1, (48u << 10) / per_wave));
+    // recent policy with fan-out <= 16: the wave finishes the in-block searches together
+    // (16 more bytes of LDS per query); otherwise each lane searches alone
+    int32_t gshift = (POLICY == 0 && a.fanout <= kCoopGroup) ? 4 : -1;
+    if (getenv("TNS_EXP_NOCOOP")) gshift = -1;
+    const size_t per_wave_all = per_wave + (gshift >= 0 ? (size_t)kWave * 16 : 0);
+    int waves = (int)std::min<size_t>(FUSED ? 16 : 4, std::max<size_t>(1, (62u << 10) / per_wave_all));
     const int64_t per_wg = (int64_t)waves * kWave;
     const int64_t grid = (a.Q + per_wg - 1) / per_wg;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
@@ -594,9 +691,9 @@ hipError_t launch_sample_t(const SampleArgs& a, hipStream_t stream) {
                            grid, a.rowptr, a.Q, a.Q_dev, a.total_out);
     }
     if (grid <= 0) return hipGetLastError();
-    const size_t lds = per_wave * waves;
+    const size_t lds = per_wave_all * waves;
     hipLaunchKernelGGL((tns_sample_kernel<POLICY, INCL, pos_t, COUNT, FUSED>), dim3((unsigned)grid), dim3(waves * kWave),
-                       lds, stream, a, stride, magic_for(a.fanout));
+                       lds, stream, a, stride, magic_for(a.fanout), gshift);
     return hipGetLastError();
 }
 

@@ -77,10 +77,16 @@ __device__ __forceinline__ int64_t lookback_exclusive(ScanWorkspace* ws, int64_t
     int64_t excl = 0;
     int64_t idx = tile - 1;
     int spins = 0;
+    bool fresh = true;              // new window: every lane reads its tile's state
+    uint64_t st = 0;
     while (true) {
         const int64_t t = idx - lane;
-        uint64_t st = kStPrefix;   // before the first tile: prefix 0
-        if (t >= 0) st = __hip_atomic_load(&ws->status[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // a lane re-reads only while its tile is not ready
+        if (fresh || (st & kStMask) == 0) {
+            st = kStPrefix;         // before the first tile: prefix 0
+            if (t >= 0) st = __hip_atomic_load(&ws->status[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        fresh = false;
         const uint64_t state = st & kStMask;
         const uint64_t is_prefix = __ballot(state == kStPrefix);
         const uint64_t not_ready = __ballot(state == 0);
@@ -91,7 +97,7 @@ __device__ __forceinline__ int64_t lookback_exclusive(ScanWorkspace* ws, int64_t
                 if (lane == 0) atomicExch(&ws->error, 1u);
                 return excl;
             }
-            __builtin_amdgcn_s_sleep(2);
+            __builtin_amdgcn_s_sleep(16);      // ~0.4 us between polls: late tiles are late by microseconds
             continue;
         }
         int64_t v = (lane <= first) ? (int64_t)(st & ~kStMask) : 0;
@@ -99,6 +105,7 @@ __device__ __forceinline__ int64_t lookback_exclusive(ScanWorkspace* ws, int64_t
         excl += v;
         if (first < kWave) return excl;
         idx -= kWave;
+        fresh = true;
     }
 }
 
@@ -679,7 +686,6 @@ hipError_t launch_sample_t(const SampleArgs& a, hipStream_t stream) {
     // recent policy with fan-out <= 16: the wave finishes the in-block searches together
     // (16 more bytes of LDS per query); otherwise each lane searches alone
     int32_t gshift = (POLICY == 0 && a.fanout <= kCoopGroup) ? 4 : -1;
-    if (getenv("TNS_EXP_NOCOOP")) gshift = -1;
     const size_t per_wave_all = per_wave + (gshift >= 0 ? (size_t)kWave * 16 : 0);
     int waves = (int)std::min<size_t>(FUSED ? 16 : 4, std::max<size_t>(1, (62u << 10) / per_wave_all));
     const int64_t per_wg = (int64_t)waves * kWave;

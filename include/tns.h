@@ -98,13 +98,33 @@ TNS_API int tns_set_sampler(tns_plan *plan, int32_t fanout, int32_t policy, int3
  * min(degree so far, tau))).  All arrays are HOST, length m, in arrival order; the edge
  * src[i] -> dst[i] is stored with its source node (directed storage; store both directions
  * yourself for an undirected graph).  eid may be NULL: ids then continue a per-instance
- * running counter.  Inside the batch a node's edges are put in timestamp order (stable);
+ * running counter; given ids must be >= 0 (TNS_EINVAL otherwise).  Inside the batch a node's edges are put in timestamp order (stable);
  * TNS_EORDER if a node would receive an edge older than its newest stored edge or a NaN
  * time, TNS_ERANGE for src outside [0, num_nodes).  Nothing is visible to tns_run until
  * tns_commit.
  */
 TNS_API int tns_add_edges(tns_plan *plan, int32_t instance, const int32_t *src, const int32_t *dst,
                   const float *ts, const int32_t *eid, int64_t m);
+
+/*
+ * Tombstone deletion (section 4.1: validity fields are cleared while data layouts and pointers
+ * are preserved; invalid nodes and edges are ignored during sampling).
+ *
+ * tns_delete_edges: HOST arrays of m (source node, edge id) pairs of instance `instance`.  A
+ * deleted edge is treated as absent by every later tns_run (after the next tns_commit): it is
+ * neither counted as a candidate nor returned.  *num_deleted (may be NULL) receives how many
+ * stored edges matched.  Edge ids must therefore be non-negative (tns_add_edges rejects negative
+ * ids): the store marks a deleted edge by complementing its id.  Cost: a scan of the node's
+ * edges per pair on the host; on the device, a query that meets a block holding deleted edges
+ * checks that block's candidates one by one.
+ *
+ * tns_delete_nodes: HOST array of m node ids; a deleted node (deleted != 0) returns no neighbours
+ * as a target; deleted = 0 restores it.  Edges that point TO a deleted node are not filtered:
+ * delete them with tns_delete_edges.
+ */
+TNS_API int tns_delete_edges(tns_plan *plan, int32_t instance, const int32_t *src, const int32_t *eid,
+                             int64_t m, int64_t *num_deleted);
+TNS_API int tns_delete_nodes(tns_plan *plan, int32_t instance, const int32_t *nodes, int64_t m, int32_t deleted);
 
 /*
  * Make everything ingested so far visible to tns_run: uploads the changed parts of the

@@ -22,7 +22,7 @@ TNS_MAX_FANOUT = 64
 TNS_FLAG_NO_XCD_REMAP = 1
 TNS_FLAG_NO_NODE_SLAB = 2
 
-EXPORTS = ["tns_plan_create", "tns_set_sampler", "tns_add_edges", "tns_commit", "tns_workspace", "tns_run", "tns_workspace_khop", "tns_run_khop", "tns_compact", "tns_traffic_model", "tns_stats",
+EXPORTS = ["tns_plan_create", "tns_set_sampler", "tns_add_edges", "tns_delete_edges", "tns_delete_nodes", "tns_commit", "tns_workspace", "tns_run", "tns_workspace_khop", "tns_run_khop", "tns_compact", "tns_traffic_model", "tns_stats",
            "tns_node_blocks", "tns_destroy", "tns_strerror", "tns_last_error"]
 
 
@@ -68,6 +68,10 @@ def lib():
         L.tns_set_sampler.restype = C.c_int
         L.tns_add_edges.argtypes = [vp, C.c_int32, i32p, i32p, f32p, i32p, C.c_int64]
         L.tns_add_edges.restype = C.c_int
+        L.tns_delete_edges.argtypes = [vp, C.c_int32, i32p, i32p, C.c_int64, i64p]
+        L.tns_delete_edges.restype = C.c_int
+        L.tns_delete_nodes.argtypes = [vp, C.c_int32, i32p, C.c_int64, C.c_int32]
+        L.tns_delete_nodes.restype = C.c_int
         L.tns_commit.argtypes = [vp, vp]
         L.tns_commit.restype = C.c_int
         L.tns_workspace.argtypes = [vp, C.c_int64, C.POINTER(C.c_size_t)]
@@ -134,6 +138,21 @@ def tns_add_edges(plan, instance: int, src, dst, ts, eid=None) -> None:
     if not (len(src_a) == len(dst_a) == len(ts_a)) or (eid_a is not None and len(eid_a) != len(src_a)):
         raise ValueError("src, dst, ts (and eid) must have the same length")
     _check(lib().tns_add_edges(plan, instance, src_p, dst_p, ts_p, eid_p, len(src_a)), "tns_add_edges")
+
+
+def tns_delete_edges(plan, instance: int, src, eid) -> int:
+    src_a, src_p = _np(src, np.int32)
+    eid_a, eid_p = _np(eid, np.int32)
+    if len(src_a) != len(eid_a):
+        raise ValueError("src and eid must have the same length")
+    n = C.c_int64()
+    _check(lib().tns_delete_edges(plan, instance, src_p, eid_p, len(src_a), C.byref(n)), "tns_delete_edges")
+    return int(n.value)
+
+
+def tns_delete_nodes(plan, instance: int, nodes, deleted: bool = True) -> None:
+    a, p = _np(nodes, np.int32)
+    _check(lib().tns_delete_nodes(plan, instance, p, len(a), 1 if deleted else 0), "tns_delete_nodes")
 
 
 def tns_commit(plan, hip_stream: int = 0) -> None:

@@ -162,6 +162,35 @@ int tns_add_edges(tns_plan* plan, int32_t instance, const int32_t* src, const in
     }
 }
 
+int tns_delete_edges(tns_plan* plan, int32_t instance, const int32_t* src, const int32_t* eid, int64_t m,
+                     int64_t* num_deleted) {
+    g_err.clear();
+    if (!plan) return fail(TNS_EINVAL, "null plan");
+    if (m < 0 || (m > 0 && (!src || !eid))) return fail(TNS_EINVAL, "null array or negative count");
+    tns::Store& s = *plan->store;
+    if (instance < 0 || instance >= s.config().num_instances) return fail(TNS_ERANGE, "instance out of range");
+    for (int64_t i = 0; i < m; ++i) {
+        if (src[i] < 0 || src[i] >= s.config().num_nodes) return fail(TNS_ERANGE, "node id outside [0, num_nodes)");
+        if (eid[i] < 0) return fail(TNS_EINVAL, "negative edge id");
+    }
+    int64_t hit = 0;
+    for (int64_t i = 0; i < m; ++i) hit += s.delete_edge(instance, src[i], eid[i]);
+    if (num_deleted) *num_deleted = hit;
+    return TNS_OK;
+}
+
+int tns_delete_nodes(tns_plan* plan, int32_t instance, const int32_t* nodes, int64_t m, int32_t deleted) {
+    g_err.clear();
+    if (!plan) return fail(TNS_EINVAL, "null plan");
+    if (m < 0 || (m > 0 && !nodes)) return fail(TNS_EINVAL, "null array or negative count");
+    tns::Store& s = *plan->store;
+    if (instance < 0 || instance >= s.config().num_instances) return fail(TNS_ERANGE, "instance out of range");
+    for (int64_t i = 0; i < m; ++i)
+        if (nodes[i] < 0 || nodes[i] >= s.config().num_nodes) return fail(TNS_ERANGE, "node id outside [0, num_nodes)");
+    for (int64_t i = 0; i < m; ++i) s.set_node_deleted(instance, nodes[i], deleted != 0);
+    return TNS_OK;
+}
+
 int tns_commit(tns_plan* plan, void* hip_stream) {
     g_err.clear();
     if (!plan) return fail(TNS_EINVAL, "null plan");

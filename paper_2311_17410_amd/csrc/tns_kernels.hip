@@ -63,7 +63,7 @@ __device__ __forceinline__ int32_t wave_inclusive_scan(int32_t v, int lane) {
 constexpr uint64_t kStTotal = 1ull << 62, kStPrefix = 2ull << 62, kStMask = 3ull << 62;
 constexpr int kSpinLimit = 1 << 22;
 constexpr int kCoopGroup = 16;        // lanes per query in the cooperative search (recent policy, fan-out <= 16)
-constexpr int kFusedRegSlots = 10;   // fan-outs up to this keep the gathered edges in registers (fused variant)
+constexpr int kGatherChunk = 10;      // gather iterations whose loads are issued together
 
 struct ScanWorkspace {
     uint32_t ticket;
@@ -126,6 +126,11 @@ __global__ void __launch_bounds__(256) tns_scan_init(ScanWorkspace* ws, int64_t 
     if (i < num_tiles) ws->status[i] = 0;
 }
 
+// Unsigned index type of the same width as the LDS position entries: with a 32-bit index the edge
+// load is addressed as base + 32-bit offset, one register per address.
+template <typename pos_t> struct index_of { using type = uint64_t; };
+template <> struct index_of<int32_t> { using type = uint32_t; };
+
 // State of one lane's walk over the blocks of its target node, newest block first
 // (Algorithm 1).  `t` numbers the blocks in visiting order.
 template <int POLICY, bool INCL, typename pos_t>
@@ -170,7 +175,8 @@ struct Walk {
         // candidate range [lo, hi) of the block; t_min / t_max settle most cases without a search
         int32_t hi = size;
         const bool all_before_end = INCL ? (te >= r.t_max) : (te > r.t_max);
-        if (POLICY == 0 && group > 0 && !all_before_end && !(tb > r.t_min)) {
+        const bool tomb = rec_tombstones(r);   // some edges of the block are deleted: they count as absent
+        if (POLICY == 0 && group > 0 && !tomb && !all_before_end && !(tb > r.t_min)) {
             // only the newest overlapping block can contain the window end, so nothing is recorded yet
             int32_t lo = 0;
             while (hi - lo > group) {
@@ -187,8 +193,24 @@ struct Walk {
         if (!all_before_end) hi = first_not_before<INCL>(off, size, te);
         int32_t lo = 0;
         if (tb > r.t_min) lo = first_not_before<false>(off, hi, tb);
-        const int32_t cnt = hi - lo;
-        if (cnt > 0) {
+        int32_t cnt = hi - lo;
+        if (tomb) {
+            // slow path: look at every candidate's validity (the edge id word), newest first
+            cnt = 0;
+            for (int32_t i = hi - 1; i >= lo; --i) {
+                const int32_t id = (int32_t)edges[slot_word(off + i) + 2];
+                ++n_probes;
+                if (id < 0) continue;
+                if (k < f) s_pos[k++] = (pos_t)slot_word(off + i);
+                ++cnt;
+                if (POLICY == 0 && k >= f) break;
+            }
+            if (POLICY == 1 && cnt > 0) {
+                if (t_first < 0) { t_first = t; hi_first = hi; }
+                t_last = t; lo_last = lo;
+                c += cnt;
+            }
+        } else if (cnt > 0) {
             const int32_t take = min(f - k, cnt);
             for (int32_t j = 0; j < take; ++j) s_pos[k + j] = (pos_t)slot_word(off + hi - 1 - j);
             k += take > 0 ? take : 0;
@@ -217,13 +239,26 @@ struct Walk {
         ++n_blocks;
         const int32_t hi = (t == t_first) ? hi_first : rec_size(r);
         const int32_t lo = (t == t_last) ? lo_last : 0;
-        const int64_t cnt = hi - lo;
+        int64_t cnt = hi - lo;
         const int64_t off = rec_off(r);
-        for (int32_t j = 0; j < f; ++j) {
-            const int64_t sv = (int64_t)s_pos[j];
-            if (sv < 0) {
-                const int64_t rr = -(sv + 1) - cum;
-                if (rr < cnt) s_pos[j] = (pos_t)slot_word(off + hi - 1 - rr);
+        if (rec_tombstones(r)) {
+            // ranks count valid edges only: walk them newest first
+            cnt = 0;
+            for (int32_t i = hi - 1; i >= lo; --i) {
+                if ((int32_t)edges[slot_word(off + i) + 2] < 0) continue;
+                for (int32_t j = 0; j < f; ++j) {
+                    const int64_t sv = (int64_t)s_pos[j];
+                    if (sv < 0 && -(sv + 1) - cum == cnt) s_pos[j] = (pos_t)slot_word(off + i);
+                }
+                ++cnt;
+            }
+        } else {
+            for (int32_t j = 0; j < f; ++j) {
+                const int64_t sv = (int64_t)s_pos[j];
+                if (sv < 0) {
+                    const int64_t rr = -(sv + 1) - cum;
+                    if (rr < cnt) s_pos[j] = (pos_t)slot_word(off + hi - 1 - rr);
+                }
             }
         }
         cum += cnt;
@@ -245,11 +280,74 @@ __device__ __forceinline__ int64_t shfl64(int64_t v, int src) {
 
 // Word index of the edge in slot j of a query: the first hq slots come from the block whose
 // search the wave finished (newest first), the others from the positions the lane recorded.
+// The wave's cooperative gather: its 64*f slots in flat order, lane l handles slot it*64 + l, so
+// consecutive lanes read consecutive edges of one query (12-byte loads within one or two lines)
+// and every store instruction covers 256 consecutive bytes of an output array.  The loads of up to
+// kGatherChunk iterations are issued together, into registers, before anything is stored: the
+// wave pays the memory latency once per batch instead of once per slot.
+struct GatherRegs {
+    int32_t nbr[kGatherChunk], eid[kGatherChunk];     // eid < 0: empty slot (edge ids are non-negative)
+    float ts[kGatherChunk];
+};
+
 template <typename pos_t>
-__device__ __forceinline__ int64_t slot_position(const pos_t* __restrict__ w_pos, int32_t stride, uint32_t ql, int32_t j,
-                                                 int32_t hq, int64_t dq) {
-    if (j < hq) return slot_word(dq + hq - 1 - j);
-    return (int64_t)w_pos[ql * stride + (j - hq)];
+__device__ __forceinline__ void gather_load(GatherRegs& g, const SampleArgs& p, uint32_t f_magic, int32_t stride,
+                                            const pos_t* __restrict__ w_pos, int lane, int32_t it0, int32_t k) {
+    const int32_t f = p.fanout;
+#pragma unroll
+    for (int i = 0; i < kGatherChunk; ++i) {
+        g.nbr[i] = -1; g.eid[i] = -1; g.ts[i] = 0.0f;
+        if (it0 + i < f) {
+            const uint32_t s = (uint32_t)((it0 + i) * kWave + lane);
+            const uint32_t ql = div_by(s, (uint32_t)f, f_magic);
+            const int32_t j = (int32_t)(s - ql * (uint32_t)f);
+            const int32_t kq = __shfl(k, (int)ql, kWave);
+            if (j < kq) {
+                const auto pos = (typename index_of<pos_t>::type)w_pos[ql * stride + j];
+                const Edge e = *reinterpret_cast<const Edge*>(p.edges + pos);
+                g.nbr[i] = e.nbr; g.eid[i] = e.eid; g.ts[i] = e.ts;
+            }
+        }
+    }
+}
+
+// padded rows: slots of queries below Q, empty slots get the sentinels
+__device__ __forceinline__ void store_padded(const GatherRegs& g, const SampleArgs& p, uint32_t f_magic, int lane,
+                                             int32_t it0, int64_t q0, int64_t Q) {
+    const int32_t f = p.fanout;
+    const int64_t out0 = q0 * f;
+#pragma unroll
+    for (int i = 0; i < kGatherChunk; ++i) {
+        if (it0 + i < f) {
+            const uint32_t s = (uint32_t)((it0 + i) * kWave + lane);
+            const uint32_t ql = div_by(s, (uint32_t)f, f_magic);
+            if (q0 + (int64_t)ql < Q) {
+                p.out_nbr[out0 + s] = g.nbr[i];
+                p.out_eid[out0 + s] = g.eid[i];
+                p.out_ts[out0 + s] = g.ts[i];
+            }
+        }
+    }
+}
+
+// dense copy: `row` = where the lane's own query starts; consecutive lanes write consecutive entries
+__device__ __forceinline__ void store_dense(const GatherRegs& g, const SampleArgs& p, uint32_t f_magic, int lane,
+                                            int32_t it0, int64_t row) {
+    const int32_t f = p.fanout;
+#pragma unroll
+    for (int i = 0; i < kGatherChunk; ++i) {
+        if (it0 + i < f) {
+            const uint32_t s = (uint32_t)((it0 + i) * kWave + lane);
+            const uint32_t ql = div_by(s, (uint32_t)f, f_magic);
+            const int32_t j = (int32_t)(s - ql * (uint32_t)f);
+            const int64_t rowq = shfl64(row, (int)ql);
+            if (g.eid[i] >= 0) {
+                p.cmp_nbr[rowq + j] = g.nbr[i];
+                p.cmp_eid[rowq + j] = g.eid[i];
+                p.cmp_ts[rowq + j] = g.ts[i];
+            }
+        }
+    }
 }
 
 __device__ __forceinline__ BlockRec as_rec(const uint4& u) {
@@ -384,7 +482,10 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
         for (int it = 0; it < G; ++it) {
             const uint2 d = s_q[it * groups + g];
             tj[it] = 0.0f;
-            if (j < (int32_t)(d.y >> 8)) tj[it] = __uint_as_float(p.edges[slot_word((((int64_t)(d.y & 0xffu)) << 32 | d.x) + j)]);
+            if (j < (int32_t)(d.y >> 8)) {
+                const auto w = (typename index_of<pos_t>::type)slot_word((((int64_t)(d.y & 0xffu)) << 32 | d.x) + j);
+                tj[it] = __uint_as_float(p.edges[w]);
+            }
         }
 #pragma unroll
         for (int it = 0; it < G; ++it) {
@@ -398,7 +499,13 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
         if (w.d_off >= 0) h = w.d_lo + s_h[lane];
     }
     const int32_t k = POLICY == 0 ? min(f, h + w.k) : w.k;
-    const int64_t d_off = w.d_off;
+    if (POLICY == 0 && h > 0) {
+        // The first min(h, f) slots come from the block whose search the wave finished (newest
+        // first); the positions recorded from older blocks move up behind them.
+        const int32_t hh = min(h, f);
+        for (int32_t j = k - 1; j >= hh; --j) w.s_pos[j] = w.s_pos[j - hh];
+        for (int32_t j = 0; j < hh; ++j) w.s_pos[j] = (pos_t)slot_word(w.d_off + h - 1 - j);
+    }
     if (COUNT) {
         // totals of what this launch reads: node entries, block records, timestamp probes, edges
         unsigned long long v4[4] = {(unsigned long long)n_nodes, (unsigned long long)w.n_blocks,
@@ -412,7 +519,6 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
         return;
     }
     const pos_t* __restrict__ w_pos = reinterpret_cast<const pos_t*>(smem) + (size_t)wave * kWave * stride;
-    const int64_t out0 = q0 * f;
 
     if (FUSED) {
         // Chained scan over the workgroup tiles for the dense offsets.
@@ -437,122 +543,46 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
                 s_tile_base = excl;
             }
         };
-        // one loop that gathers and writes both the padded row and the dense copy; needs the tile offset
-        auto gather_both = [&]() {
-            const int64_t row = s_tile_base + wave_off + (inc - k);
+        auto write_rowptr = [&](int64_t row) {
             if (q < Q) {
                 p.rowptr[q] = row;
                 if (q == Q - 1) {
                     p.rowptr[Q] = row + k;
                     if (p.total_out) *p.total_out = row + k;
-                }
-            }
-            for (int32_t it = 0; it < f; ++it) {
-                const uint32_t s = (uint32_t)(it * kWave + lane);
-                const uint32_t ql = div_by(s, (uint32_t)f, f_magic);
-                const int32_t j = (int32_t)(s - ql * (uint32_t)f);
-                const int32_t kq = __shfl(k, (int)ql, kWave);
-                const int32_t hq = POLICY == 0 ? __shfl(h, (int)ql, kWave) : 0;
-                const int64_t dq = POLICY == 0 ? shfl64(d_off, (int)ql) : 0;
-                const int64_t rowq = __shfl(row, (int)ql, kWave);
-                if (q0 + (int64_t)ql < Q) {
-                    int32_t nbr = -1, eid = -1;
-                    float t = 0.0f;
-                    if (j < kq) {
-                        const int64_t pos = slot_position(w_pos, stride, ql, j, hq, dq);
-                        const Edge e = *reinterpret_cast<const Edge*>(p.edges + pos);
-                        nbr = e.nbr; eid = e.eid; t = e.ts;
-                        p.cmp_nbr[rowq + j] = nbr;
-                        p.cmp_eid[rowq + j] = eid;
-                        p.cmp_ts[rowq + j] = t;
-                    }
-                    p.out_nbr[out0 + s] = nbr;
-                    p.out_eid[out0 + s] = eid;
-                    p.out_ts[out0 + s] = t;
                 }
             }
         };
-        if (f <= kFusedRegSlots) {
-            // Every wave first gathers and writes its padded rows; the gathered edges stay in
-            // registers.  Wave 0 then looks back for the tile offset (the earlier tiles have had
-            // the time of a gather to publish their totals), and only the dense copy waits for it.
-            int32_t vn[kFusedRegSlots], ve[kFusedRegSlots];
-            float vt[kFusedRegSlots];
-#pragma unroll
-            for (int it = 0; it < kFusedRegSlots; ++it) {
-                vn[it] = -1; ve[it] = -1; vt[it] = 0.0f;
-                if (it < f) {
-                    const uint32_t s = (uint32_t)(it * kWave + lane);
-                    const uint32_t ql = div_by(s, (uint32_t)f, f_magic);
-                    const int32_t j = (int32_t)(s - ql * (uint32_t)f);
-                    const int32_t kq = __shfl(k, (int)ql, kWave);
-                    const int32_t hq = POLICY == 0 ? __shfl(h, (int)ql, kWave) : 0;
-                    const int64_t dq = POLICY == 0 ? shfl64(d_off, (int)ql) : 0;
-                    if (j < kq) {
-                        const int64_t pos = slot_position(w_pos, stride, ql, j, hq, dq);
-                        const Edge e = *reinterpret_cast<const Edge*>(p.edges + pos);
-                        vn[it] = e.nbr; ve[it] = e.eid; vt[it] = e.ts;
-                    }
-                    if (q0 + (int64_t)ql < Q) {
-                        p.out_nbr[out0 + s] = vn[it];
-                        p.out_eid[out0 + s] = ve[it];
-                        p.out_ts[out0 + s] = vt[it];
-                    }
-                }
-            }
+        GatherRegs g;
+        if (f <= kGatherChunk) {
+            // Every wave first gathers (one batch of loads) and writes its padded rows; the gathered
+            // edges stay in registers.  Wave 0 then looks back for the tile offset (the earlier
+            // tiles have had the time of a gather to publish their totals), and only the dense
+            // copy waits for it.
+            gather_load(g, p, f_magic, stride, w_pos, lane, 0, k);
+            store_padded(g, p, f_magic, lane, 0, q0, Q);
             if (wave == 0) chain();
             __syncthreads();
             const int64_t row = s_tile_base + wave_off + (inc - k);
-            if (q < Q) {
-                p.rowptr[q] = row;
-                if (q == Q - 1) {
-                    p.rowptr[Q] = row + k;
-                    if (p.total_out) *p.total_out = row + k;
-                }
-            }
-#pragma unroll
-            for (int it = 0; it < kFusedRegSlots; ++it) {
-                if (it < f) {
-                    const uint32_t s = (uint32_t)(it * kWave + lane);
-                    const uint32_t ql = div_by(s, (uint32_t)f, f_magic);
-                    const int32_t j = (int32_t)(s - ql * (uint32_t)f);
-                    const int32_t kq = __shfl(k, (int)ql, kWave);
-                    const int64_t rowq = __shfl(row, (int)ql, kWave);
-                    if (j < kq) {       // consecutive lanes write consecutive dense entries
-                        p.cmp_nbr[rowq + j] = vn[it];
-                        p.cmp_eid[rowq + j] = ve[it];
-                        p.cmp_ts[rowq + j] = vt[it];
-                    }
-                }
-            }
+            write_rowptr(row);
+            store_dense(g, p, f_magic, lane, 0, row);
         } else {
-            // larger fan-outs: offset first, then one loop gathers and writes both
+            // larger fan-outs: offset first, then gather in batches and write both
             if (wave == 0) chain();
             __syncthreads();
-            gather_both();
+            const int64_t row = s_tile_base + wave_off + (inc - k);
+            write_rowptr(row);
+            for (int32_t it0 = 0; it0 < f; it0 += kGatherChunk) {
+                gather_load(g, p, f_magic, stride, w_pos, lane, it0, k);
+                store_padded(g, p, f_magic, lane, it0, q0, Q);
+                store_dense(g, p, f_magic, lane, it0, row);
+            }
         }
     } else {
         wave_lds_sync();
-        // cooperative gather + padded write: the wave's 64*f slots in flat order
-        for (int32_t it = 0; it < f; ++it) {
-            const uint32_t s = (uint32_t)(it * kWave + lane);
-            const uint32_t ql = div_by(s, (uint32_t)f, f_magic);
-            const int32_t j = (int32_t)(s - ql * (uint32_t)f);
-            const int32_t kq = __shfl(k, (int)ql, kWave);
-            const int32_t hq = POLICY == 0 ? __shfl(h, (int)ql, kWave) : 0;
-            const int64_t dq = POLICY == 0 ? shfl64(d_off, (int)ql) : 0;
-            if (q0 + (int64_t)ql < Q) {
-                int32_t nbr = -1, eid = -1;
-                float t = 0.0f;
-                if (j < kq) {
-                    const int64_t pos = slot_position(w_pos, stride, ql, j, hq, dq);
-                    const Edge e = *reinterpret_cast<const Edge*>(p.edges + pos);
-                    nbr = e.nbr; eid = e.eid; t = e.ts;
-                }
-                p.out_nbr[out0 + s] = nbr;
-                p.out_eid[out0 + s] = eid;
-                p.out_ts[out0 + s] = t;
-            }
+        GatherRegs g;
+        for (int32_t it0 = 0; it0 < f; it0 += kGatherChunk) {
+            gather_load(g, p, f_magic, stride, w_pos, lane, it0, k);
+            store_padded(g, p, f_magic, lane, it0, q0, Q);
         }
     }
     if (q < Q) p.out_count[q] = k;

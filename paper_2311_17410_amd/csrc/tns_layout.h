@@ -25,13 +25,13 @@ namespace tns {
 
 constexpr int kInlineBlocks = 7;
 constexpr int64_t kMaxBlockEdges = (int64_t(1) << 24) - 1;  // size field is 24 bits
-constexpr int64_t kMaxEdgeOffset = (int64_t(1) << 40) - 1;  // offset (slot index) field is 40 bits
+constexpr int64_t kMaxEdgeOffset = (int64_t(1) << 39) - 1;  // offset (slot index) field is 39 bits
 
 // Edge block metadata (section 4.1: fill, where the edge data is, earliest and latest time).
 struct BlockRec {
     float t_min, t_max;  // earliest / latest edge time in the block
     uint32_t off_lo;     // low 32 bits of the slot index of the block's first edge
-    uint32_t size_hi;    // bits 0-23: edges held; bits 24-31: offset bits 32-39
+    uint32_t size_hi;    // bits 0-23: edges held; bits 24-30: offset bits 32-38; bit 31: block holds deleted edges
 };
 static_assert(sizeof(BlockRec) == 16, "block record is 16 bytes");
 
@@ -41,13 +41,14 @@ static_assert(sizeof(BlockRec) == 16, "block record is 16 bytes");
 #define TNS_HD inline
 #endif
 TNS_HD int32_t rec_size(const BlockRec& r) { return (int32_t)(r.size_hi & 0xffffffu); }
-TNS_HD int64_t rec_off(const BlockRec& r) { return (int64_t)r.off_lo | ((int64_t)(r.size_hi >> 24) << 32); }
-TNS_HD BlockRec make_rec(float t_min, float t_max, int64_t off, int32_t size) {
+TNS_HD int64_t rec_off(const BlockRec& r) { return (int64_t)r.off_lo | ((int64_t)((r.size_hi >> 24) & 0x7fu) << 32); }
+TNS_HD bool rec_tombstones(const BlockRec& r) { return (r.size_hi >> 31) != 0; }
+TNS_HD BlockRec make_rec(float t_min, float t_max, int64_t off, int32_t size, bool tombstones = false) {
     BlockRec r;
     r.t_min = t_min;
     r.t_max = t_max;
     r.off_lo = (uint32_t)(off & 0xffffffffu);
-    r.size_hi = ((uint32_t)size & 0xffffffu) | ((uint32_t)(off >> 32) << 24);
+    r.size_hi = ((uint32_t)size & 0xffffffu) | (((uint32_t)(off >> 32) & 0x7fu) << 24) | (tombstones ? 0x80000000u : 0u);
     return r;
 }
 
@@ -57,7 +58,7 @@ struct alignas(128) NodeLine {
     int32_t degree;    // stored edges (out-degree)
     uint32_t dir_line; // nblocks > kInlineBlocks: where the node's records start in the directory
                        // pool, in units of kDirAlign records (oldest record first)
-    int32_t flags;     // bit 0: node deleted
+    int32_t flags;     // bit 0: node deleted; bit 1: some block of the node holds deleted edges
     BlockRec rec[kInlineBlocks];  // nblocks <= kInlineBlocks: rec[0] newest ... rec[nblocks-1] oldest
 };
 static_assert(sizeof(NodeLine) == 128, "node entry is one 128-byte line");
@@ -65,6 +66,8 @@ static_assert(sizeof(NodeLine) == 128, "node entry is one 128-byte line");
 constexpr int kDirAlign = 8;  // directory runs start on a 128-byte line
 
 // One entry of the graph edge data.  Inside a block, entries are in (timestamp, arrival) order.
+// Edge ids are non-negative; a deleted edge (section 4.1: validity cleared, layout kept) stores the
+// bitwise complement of its id, so validity costs no extra word and the id stays recoverable.
 struct Edge {
     float ts;
     int32_t nbr;

@@ -110,6 +110,45 @@ void Store::append_block(int64_t nidx, NodeLine& nd, const BlockRec& r, int32_t 
     tail_cap_[(size_t)nidx] = cap;
 }
 
+int64_t Store::delete_edge(int32_t inst, int32_t v, int32_t e) {
+    const int64_t nidx = node_index(inst, v);
+    NodeLine& nd = nodes.raw(nidx);
+    int64_t hit = 0;
+    for (int32_t b = 0; b < nd.nblocks; ++b) {
+        // block records in chronological order; the record is rewritten when a tombstone is set
+        BlockRec* r = nd.nblocks <= kInlineBlocks ? &nd.rec[nd.nblocks - 1 - b]
+                                                  : &dir.raw((int64_t)nd.dir_line * kDirAlign + b);
+        const int64_t off = rec_off(*r);
+        const int32_t size = rec_size(*r);
+        bool here = false;
+        for (int32_t i = 0; i < size; ++i) {
+            Edge& ed = edge_at(off + i);
+            if (ed.eid == e) {
+                ed.eid = ~e;
+                mark_slots(off + i, 1);
+                here = true;
+                ++hit;
+            }
+        }
+        if (here) {
+            *r = make_rec(r->t_min, r->t_max, off, size, true);
+            if (nd.nblocks > kInlineBlocks) dir.mark((int64_t)nd.dir_line * kDirAlign + b, 1);
+        }
+    }
+    if (hit) {
+        nd.flags |= 2;
+        nodes.mark(nidx, 1);
+        totals_[(size_t)inst].deleted += hit;
+        any_tombstones_ = true;
+    }
+    return hit;
+}
+
+void Store::set_node_deleted(int32_t inst, int32_t v, bool deleted) {
+    NodeLine& nd = nodes.mut(node_index(inst, v));
+    nd.flags = deleted ? (nd.flags | 1) : (nd.flags & ~1);
+}
+
 namespace {
 
 // Stable LSD radix sort of batch positions by source node id (11 bits per pass).
@@ -162,7 +201,15 @@ int Store::add_edges(int32_t inst, const int32_t* src, const int32_t* dst, const
             err = "NaN timestamp at batch position " + std::to_string(i);
             return TNS_EORDER;
         }
+        if (eid && eid[i] < 0) {
+            err = "negative edge id at batch position " + std::to_string(i);
+            return TNS_EINVAL;
+        }
         if (i > 0 && ts[i - 1] > ts[i]) globally_sorted = false;
+    }
+    if (!eid && totals_[(size_t)inst].next_eid + m > (int64_t)INT32_MAX) {
+        err = "running edge id would exceed 2^31-1";
+        return TNS_ESIZE;
     }
     InstanceTotals& tot = totals_[(size_t)inst];
     // A batch that is in time order as a whole and starts no earlier than anything stored in
@@ -227,7 +274,7 @@ int Store::add_edges(int32_t inst, const int32_t* src, const int32_t* dst, const
             if (take > 0) {
                 for (int64_t k = 0; k < take; ++k) put(off + size + k, ord[i + k]);
                 mark_slots(off + size, take);
-                tb = make_rec(tb.t_min, ts[ord[i + take - 1]], off, size + (int32_t)take);
+                tb = make_rec(tb.t_min, ts[ord[i + take - 1]], off, size + (int32_t)take, rec_tombstones(tb));
                 nd.degree += (int32_t)take;
                 i += take;
             }

@@ -95,6 +95,7 @@ struct StoreConfig {
 
 struct InstanceTotals {
     int64_t edges = 0, slots = 0, blocks = 0, next_eid = 0;   // slots: sum of block capacities
+    int64_t deleted = 0;                                         // edges whose validity was cleared
     float newest_ts = 0.0f;  // newest timestamp stored so far (valid if edges > 0)
 };
 
@@ -105,6 +106,13 @@ public:
     // One ingestion batch for one instance; status codes as in tns.h, detail in err.
     int add_edges(int32_t inst, const int32_t* src, const int32_t* dst, const float* ts, const int32_t* eid,
                   int64_t m, std::string& err);
+
+    // Tombstone deletion (section 4.1): clears the validity of the edge (node v, edge id e); returns
+    // how many stored edges matched (0 or 1 for unique ids).
+    int64_t delete_edge(int32_t inst, int32_t v, int32_t e);
+    // Marks a node deleted / restores it.
+    void set_node_deleted(int32_t inst, int32_t v, bool deleted);
+    bool any_tombstones() const { return any_tombstones_; }
 
     const StoreConfig& config() const { return cfg_; }
     const InstanceTotals& totals(int32_t inst) const { return totals_[inst]; }
@@ -135,6 +143,7 @@ private:
     void append_block(int64_t nidx, NodeLine& nd, const BlockRec& r, int32_t cap);
 
     StoreConfig cfg_;
+    bool any_tombstones_ = false;
     std::vector<InstanceTotals> totals_;
     std::vector<int32_t> tail_cap_;       // capacity of each node's newest block (host side only)
     std::vector<int32_t> dir_cap_;        // records reserved for the node in the directory pool (0: inline)

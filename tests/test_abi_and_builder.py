@@ -134,3 +134,24 @@ def test_instances_are_independent_in_the_builder():
     assert B.tns_stats(h, 2)["num_edges"] == 3 and B.tns_stats(h)["num_edges"] == 5
     assert list(B.tns_node_blocks(h, 2, 0)["cap"]) == [3]
     B.tns_destroy(h)
+
+
+def test_tombstone_deletion_on_the_host():
+    h = B.tns_plan_create(num_nodes=3, fanout=2, block_threshold=4)
+    B.tns_add_edges(h, 0, [0, 0, 1, 0], [1, 2, 0, 1], [1.0, 2.0, 3.0, 4.0])
+    with pytest.raises(B.TnsError) as ei:
+        B.tns_add_edges(h, 0, [0], [1], [9.0], eid=[-5])             # ids must be non-negative
+    assert ei.value.status == B.TNS_EINVAL
+    assert B.tns_delete_edges(h, 0, [0, 0, 1], [1, 7, 0]) == 1        # (0,1) exists; (0,7) and (1,0) do not
+    assert B.tns_delete_edges(h, 0, [0], [1]) == 0                    # already deleted
+    st = B.tns_stats(h)
+    assert st["num_edges"] == 4 and st["num_blocks"] == 2             # layout preserved
+    with pytest.raises(B.TnsError) as ei:
+        B.tns_delete_edges(h, 0, [3], [0])
+    assert ei.value.status == B.TNS_ERANGE
+    with pytest.raises(B.TnsError) as ei:
+        B.tns_delete_nodes(h, 0, [5])
+    assert ei.value.status == B.TNS_ERANGE
+    B.tns_delete_nodes(h, 0, [2])
+    B.tns_delete_nodes(h, 0, [2], deleted=False)
+    B.tns_destroy(h)

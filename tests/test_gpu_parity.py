@@ -161,6 +161,51 @@ def test_standalone_compaction_equals_fused(B, oracle_lib):
     plan.close()
 
 
+# ---- deletion (tombstones) -------------------------------------------------------------------------
+
+@pytest.mark.parametrize("policy", [0, 1])
+def test_deleted_edges_and_nodes_are_ignored(B, oracle_lib, policy):
+    st = W.zipf_stream(np.random.Generator(np.random.PCG64(5)), 1 << 13, 1 << 6, 1 << 9, 1.1, "normal")   # a hub with long blocks
+    wl = wl_of(st, fanout=6, tau=64)
+    plan = build_plan(B, wl, policy, 0, seed=21)
+    rng = np.random.default_rng(3)
+    present = np.ones(st.n, np.uint8)
+    victims = rng.choice(st.n, st.n // 5, replace=False).astype(np.int32)
+    present[victims] = 0
+    assert B.tns_delete_edges(plan.handle, 0, st.src[victims], victims) == len(victims)
+    dead_nodes = np.array([3, 17], np.int32)
+    B.tns_delete_nodes(plan.handle, 0, dead_nodes)
+    targets, t_start, t_end = W.random_queries(6, st, 3000 + 11)
+    before = gpu_sample(plan, targets, t_start, t_end)              # not committed yet: still the old store
+    full = oracle_sample(oracle_lib, wl, targets, t_start, t_end, None, 6, policy, 0, 21)
+    assert_same(before, full, oracle_lib, "before commit")
+    plan.commit()
+    adj = oracle_lib.Adjacency(st.num_nodes, st.src, st.dst, st.ts, present=present)
+    for tb in (t_start, None):
+        ref = adj.sample(targets, tb, t_end, 6, policy=policy, seed=21)
+        dead = np.isin(targets, dead_nodes)                          # a deleted target returns nothing
+        ref.count[dead] = 0; ref.nbr[dead] = -1; ref.eid[dead] = -1; ref.ts[dead] = 0
+        got = gpu_sample(plan, targets, tb, t_end)
+        assert_same(got, ref, oracle_lib, f"after deletion, start={'y' if tb is not None else 'n'}")
+    # edges appended after a deletion land in the same tail blocks; the tombstones stay
+    more = W.tiny_stream(9, 500, st.num_nodes, 500, ties=False)
+    ts2 = (more.ts + st.ts[-1] + 1).astype(np.float32)
+    B.tns_add_edges(plan.handle, 0, more.src, more.dst, ts2)
+    plan.commit()
+    src_all = np.concatenate([st.src, more.src]); dst_all = np.concatenate([st.dst, more.dst]); ts_all = np.concatenate([st.ts, ts2])
+    adj2 = oracle_lib.Adjacency(st.num_nodes, src_all, dst_all, ts_all, present=np.concatenate([present, np.ones(500, np.uint8)]))
+    t_end2 = (t_end + np.float32(ts2[-1] - st.ts[-1])).astype(np.float32)
+    ref = adj2.sample(targets, None, t_end2, 6, policy=policy, seed=21)
+    dead = np.isin(targets, dead_nodes)
+    ref.count[dead] = 0; ref.nbr[dead] = -1; ref.eid[dead] = -1; ref.ts[dead] = 0
+    assert_same(gpu_sample(plan, targets, None, t_end2), ref, oracle_lib, "after append")
+    B.tns_delete_nodes(plan.handle, 0, dead_nodes, deleted=False)
+    plan.commit()
+    ref = adj2.sample(targets, None, t_end2, 6, policy=policy, seed=21)
+    assert_same(gpu_sample(plan, targets, None, t_end2), ref, oracle_lib, "after restoring the nodes")
+    plan.close()
+
+
 # ---- multi-hop --------------------------------------------------------------------------------
 
 def oracle_khop(oracle, wl, targets, t_start, t_end, inst_rowptr, fanouts, delta, policy, seed, base=0):

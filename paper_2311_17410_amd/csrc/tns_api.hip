@@ -10,11 +10,11 @@
 #include <string>
 
 #include "../../include/tns.h"
+#include "tns_internal.h"
 #include "tns_kernels.h"
 #include "tns_store.h"
 
-namespace {
-
+namespace tns {
 thread_local std::string g_err;
 
 int fail(int code, const std::string& msg) {
@@ -27,28 +27,15 @@ int fail_hip(hipError_t e, const char* what) {
     (void)hipGetLastError();
     return e == hipErrorOutOfMemory ? TNS_ENOMEM : TNS_EHIP;
 }
+void clear_error() { g_err.clear(); }
+}  // namespace tns
 
-// Switches to the plan's device for the lifetime of the object and restores the caller's.
-class DeviceGuard {
-public:
-    explicit DeviceGuard(int dev) {
-        ok_ = hipGetDevice(&prev_) == hipSuccess;
-        if (ok_ && prev_ != dev) {
-            err_ = hipSetDevice(dev);
-            switched_ = err_ == hipSuccess;
-        }
-        if (!ok_) err_ = hipErrorNoDevice;
-    }
-    ~DeviceGuard() {
-        if (switched_) (void)hipSetDevice(prev_);
-    }
-    hipError_t error() const { return err_; }
+using tns::fail;
+using tns::fail_hip;
+using tns::g_err;
+using tns::DeviceGuard;
 
-private:
-    int prev_ = 0;
-    bool ok_ = false, switched_ = false;
-    hipError_t err_ = hipSuccess;
-};
+namespace {
 
 template <class T>
 struct DeviceArray {

@@ -1,0 +1,566 @@
+// Vectorised dynamic feature cache (section 4.3 of the paper) on gfx950: C ABI of
+// include/tns_cache.h and its kernels.  Everything a fetch does is queued on the caller's stream:
+// lookup, row gather, score update, selection of the victims (radix select over the scores),
+// insertion of the missed rows.  No host round trip, no allocation.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <climits>
+#include <cmath>
+#include <cstdint>
+#include <new>
+
+#include "../../include/tns_cache.h"
+#include "tns_internal.h"
+
+using tns::DeviceGuard;
+using tns::fail;
+using tns::fail_hip;
+
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kScanTile = 1024;           // elements per workgroup in the scans
+constexpr int kNoIndex = INT_MAX;
+
+// Device-side scalars of one fetch.
+struct Ctl {
+    uint32_t prefix, mask;                // radix select: decided high bits of the threshold key
+    int32_t remaining;                    // how many entries are still to be taken among keys matching the prefix
+    int32_t m;                            // entries replaced by this update
+    int32_t n_unique;                     // distinct missed ids of the batch
+    int32_t hist[256];
+};
+
+struct CacheState {
+    int32_t* slot_of;    // [num_ids]   slot of a cached id, -1 otherwise
+    int32_t* first_idx;  // [num_ids]   scratch: first batch position of a missed id (kNoIndex between fetches)
+    int32_t* id_of;      // [capacity]  id held by a slot, -1 if empty
+    int32_t* score;      // [capacity]  recent score (LRU) / access count (LFU)
+    int32_t* touched;    // [capacity]  LRU: accessed by the current batch
+    float* rows;         // [capacity * dim]
+    unsigned long long* counters;  // hits, misses, replaced
+    int64_t* ring;       // FIFO position
+};
+
+__global__ void __launch_bounds__(256) k_fill_i32(int32_t* p, int64_t n, int32_t v) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// slot_of from id_of (after a restore)
+__global__ void __launch_bounds__(256) k_rebuild_map(const int32_t* __restrict__ id_of, int64_t capacity, int64_t num_ids,
+                                                     int32_t* __restrict__ slot_of) {
+    const int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (s < capacity) {
+        const int32_t id = id_of[s];
+        if (id >= 0 && id < num_ids) slot_of[id] = (int32_t)s;
+    }
+}
+
+// Lookup of the batch against the cache as it is before the update; accesses are recorded.
+__global__ void __launch_bounds__(256) k_lookup(CacheState c, int policy, int64_t num_ids, int64_t B,
+                                                const int32_t* __restrict__ ids, int32_t* __restrict__ slots,
+                                                uint8_t* __restrict__ hit, Ctl* ctl) {
+    const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (blockIdx.x == 0) {          // scalars of this update
+        if (threadIdx.x == 0) { ctl->prefix = 0; ctl->mask = 0; ctl->remaining = 0; ctl->m = 0; ctl->n_unique = 0; }
+        ctl->hist[threadIdx.x] = 0;
+    }
+    int is_hit = 0, is_miss = 0;
+    if (b < B) {
+        const int32_t id = ids[b];
+        int32_t s = -2;                                   // -2: id out of range
+        if (id >= 0 && id < num_ids) {
+            s = c.slot_of[id];
+            if (s >= 0) {
+                is_hit = 1;
+                if (policy == TNS_CACHE_LRU) c.touched[s] = 1;
+                else if (policy == TNS_CACHE_LFU) atomicAdd(&c.score[s], 1);
+            } else {
+                is_miss = 1;
+                atomicMin(&c.first_idx[id], (int32_t)b);  // first occurrence of a missed id
+            }
+        }
+        slots[b] = s;
+        if (hit) hit[b] = (uint8_t)is_hit;
+    }
+    const unsigned long long h = __popcll(__ballot(is_hit)), m = __popcll(__ballot(is_miss));
+    if ((threadIdx.x & (kWave - 1)) == 0) {
+        if (h) atomicAdd(&c.counters[0], h);
+        if (m) atomicAdd(&c.counters[1], m);
+    }
+}
+
+// out[b] = cached row or row of the backing store; VEC floats per thread, rows stay coalesced
+template <int VEC>
+__global__ void __launch_bounds__(256) k_gather(const float* __restrict__ rows, const float* __restrict__ store, int32_t dim,
+                                                int64_t B, const int32_t* __restrict__ ids,
+                                                const int32_t* __restrict__ slots, float* __restrict__ out) {
+    const int32_t per_row = dim / VEC;
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= B * per_row) return;
+    const int64_t b = t / per_row;
+    const int32_t col = (int32_t)(t - b * per_row) * VEC;
+    const int32_t s = slots[b];
+    if (VEC == 4) {
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (s >= 0) v = *reinterpret_cast<const float4*>(rows + (int64_t)s * dim + col);
+        else if (s == -1) v = *reinterpret_cast<const float4*>(store + (int64_t)ids[b] * dim + col);
+        *reinterpret_cast<float4*>(out + b * dim + col) = v;
+    } else {
+        float v = 0.f;
+        if (s >= 0) v = rows[(int64_t)s * dim + col];
+        else if (s == -1) v = store[(int64_t)ids[b] * dim + col];
+        out[b * dim + col] = v;
+    }
+}
+
+// LRU: every score is decremented, accessed entries are reset to 0
+__global__ void __launch_bounds__(256) k_lru_scores(int32_t* __restrict__ score, int32_t* __restrict__ touched, int64_t capacity) {
+    const int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (s < capacity) {
+        score[s] = touched[s] ? 0 : score[s] - 1;
+        touched[s] = 0;
+    }
+}
+
+// flag[b] = 1 for the first occurrence of each missed id
+__global__ void __launch_bounds__(256) k_mark_first(const int32_t* __restrict__ first_idx, int64_t B,
+                                                    const int32_t* __restrict__ ids, const int32_t* __restrict__ slots,
+                                                    int32_t* __restrict__ flag) {
+    const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (b < B) flag[b] = (slots[b] == -1 && first_idx[ids[b]] == (int32_t)b) ? 1 : 0;
+}
+
+// ---- exclusive scan of an int32 array, in place (three kernels) ------------------------------
+
+__device__ __forceinline__ int32_t wave_inclusive_scan(int32_t v, int lane) {
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int32_t u = __shfl_up(v, d, kWave);
+        if (lane >= d) v += u;
+    }
+    return v;
+}
+
+__global__ void __launch_bounds__(256) k_scan_tile_sums(const int32_t* __restrict__ a, int64_t n, int32_t* __restrict__ sums) {
+    __shared__ int32_t s_w[4];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile;
+    int32_t v = 0;
+#pragma unroll
+    for (int i = 0; i < kScanTile / 256; ++i) {
+        const int64_t k = base + i * 256 + threadIdx.x;
+        if (k < n) v += a[k];
+    }
+    const int lane = threadIdx.x & 63;
+    v = wave_inclusive_scan(v, lane);
+    if (lane == 63) s_w[threadIdx.x >> 6] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) sums[blockIdx.x] = s_w[0] + s_w[1] + s_w[2] + s_w[3];
+}
+
+// one workgroup: exclusive scan of the tile sums; total -> *total
+__global__ void __launch_bounds__(1024) k_scan_sums(int32_t* __restrict__ sums, int64_t num_tiles, int32_t* __restrict__ total) {
+    __shared__ int32_t s_w[16];
+    __shared__ int32_t s_carry;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (threadIdx.x == 0) s_carry = 0;
+    __syncthreads();
+    for (int64_t base = 0; base < num_tiles; base += 1024) {
+        const int64_t i = base + threadIdx.x;
+        const int32_t v = i < num_tiles ? sums[i] : 0;
+        const int32_t inc = wave_inclusive_scan(v, lane);
+        if (lane == 63) s_w[wave] = inc;
+        __syncthreads();
+        int32_t wave_off = 0, all = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            const int32_t t = s_w[w];
+            if (w < wave) wave_off += t;
+            all += t;
+        }
+        const int32_t carry = s_carry;
+        if (i < num_tiles) sums[i] = carry + wave_off + (inc - v);
+        __syncthreads();
+        if (threadIdx.x == 0) s_carry = carry + all;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *total = s_carry;
+}
+
+__global__ void __launch_bounds__(256) k_scan_apply(int32_t* __restrict__ a, int64_t n, const int32_t* __restrict__ sums) {
+    __shared__ int32_t s_w[4];
+    constexpr int kPer = kScanTile / 256;
+    const int64_t base = (int64_t)blockIdx.x * kScanTile;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int32_t c[kPer], sum = 0;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        const int64_t k = base + threadIdx.x * kPer + i;
+        c[i] = k < n ? a[k] : 0;
+        sum += c[i];
+    }
+    const int32_t inc = wave_inclusive_scan(sum, lane);
+    if (lane == 63) s_w[wave] = inc;
+    __syncthreads();
+    int32_t excl = sums[blockIdx.x] + inc - sum;
+    for (int w = 0; w < wave; ++w) excl += s_w[w];
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        const int64_t k = base + threadIdx.x * kPer + i;
+        if (k < n) a[k] = excl;
+        excl += c[i];
+    }
+}
+
+// new_ids[pos] = id for the first occurrences (pos = scanned flag), up to max_replace of them;
+// every missed row clears its id's scratch entry; m = min(distinct misses, max_replace)
+__global__ void __launch_bounds__(256) k_collect_new(int32_t* __restrict__ first_idx, int64_t B, const int32_t* __restrict__ ids,
+                                                     const int32_t* __restrict__ slots, const int32_t* __restrict__ pos,
+                                                     int32_t max_replace, int32_t* __restrict__ new_ids, Ctl* ctl) {
+    const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (b == 0) {
+        const int32_t m = min(ctl->n_unique, max_replace);
+        ctl->m = m;
+        ctl->remaining = m;
+    }
+    if (b < B && slots[b] == -1) {
+        const int32_t id = ids[b];
+        if (first_idx[id] == (int32_t)b && pos[b] < max_replace) new_ids[pos[b]] = id;
+    }
+}
+__global__ void __launch_bounds__(256) k_clear_first(int32_t* __restrict__ first_idx, int64_t B, const int32_t* __restrict__ ids,
+                                                     const int32_t* __restrict__ slots) {
+    const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (b < B && slots[b] == -1) first_idx[ids[b]] = kNoIndex;
+}
+
+// ---- victims: the m entries with the lowest (score, slot) --------------------------------------
+
+__device__ __forceinline__ uint32_t score_key(int32_t score) { return (uint32_t)score ^ 0x80000000u; }   // unsigned order = signed order
+
+// histogram of one 8-bit digit over the entries whose decided high bits match
+__global__ void __launch_bounds__(256) k_select_hist(const int32_t* __restrict__ score, int64_t capacity, int shift, Ctl* ctl) {
+    __shared__ int32_t s_h[256];
+    if (ctl->m == 0) return;
+    s_h[threadIdx.x] = 0;
+    __syncthreads();
+    const uint32_t prefix = ctl->prefix, mask = ctl->mask;
+    for (int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x; s < capacity; s += (int64_t)gridDim.x * 256) {
+        const uint32_t k = score_key(score[s]);
+        if ((k & mask) == prefix) atomicAdd(&s_h[(k >> shift) & 255u], 1);
+    }
+    __syncthreads();
+    if (s_h[threadIdx.x]) atomicAdd(&ctl->hist[threadIdx.x], s_h[threadIdx.x]);
+}
+
+// pick the digit in which the remaining-th smallest key falls; clears the histogram
+__global__ void __launch_bounds__(256) k_select_digit(int shift, Ctl* ctl) {
+    __shared__ int32_t s_h[256];
+    s_h[threadIdx.x] = ctl->hist[threadIdx.x];
+    __syncthreads();
+    ctl->hist[threadIdx.x] = 0;
+    if (threadIdx.x == 0 && ctl->m > 0) {
+        int32_t rem = ctl->remaining, cum = 0;
+        int d = 0;
+        for (; d < 255; ++d) {
+            if (cum + s_h[d] >= rem) break;
+            cum += s_h[d];
+        }
+        ctl->prefix |= (uint32_t)d << shift;
+        ctl->mask |= 255u << shift;
+        ctl->remaining = rem - cum;               // entries to take among keys equal to the threshold so far
+    }
+}
+
+// eq[s] = 1 where the key equals the threshold (to rank the ties by slot)
+__global__ void __launch_bounds__(256) k_flag_equal(const int32_t* __restrict__ score, int64_t capacity, const Ctl* ctl,
+                                                    int32_t* __restrict__ eq) {
+    const int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (s < capacity) eq[s] = (ctl->m > 0 && score_key(score[s]) == ctl->prefix) ? 1 : 0;
+}
+// take[s] = key below the threshold, or equal to it and among the first `remaining` of the ties
+__global__ void __launch_bounds__(256) k_flag_take(const int32_t* __restrict__ score, int64_t capacity, const Ctl* ctl,
+                                                   const int32_t* __restrict__ eq_rank, int32_t* __restrict__ take) {
+    const int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (s < capacity) {
+        int t = 0;
+        if (ctl->m > 0) {
+            const uint32_t k = score_key(score[s]);
+            t = k < ctl->prefix || (k == ctl->prefix && eq_rank[s] < ctl->remaining);
+        }
+        take[s] = t;
+    }
+}
+// victims[pos] = slot, in ascending slot order (needs the flags again: recomputed)
+__global__ void __launch_bounds__(256) k_collect_victims(const int32_t* __restrict__ score, int64_t capacity, const Ctl* ctl,
+                                                         const int32_t* __restrict__ eq_rank, const int32_t* __restrict__ pos,
+                                                         int32_t* __restrict__ victims) {
+    const int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (s < capacity && ctl->m > 0) {
+        const uint32_t k = score_key(score[s]);
+        if (k < ctl->prefix || (k == ctl->prefix && eq_rank[s] < ctl->remaining)) victims[pos[s]] = (int32_t)s;
+    }
+}
+__global__ void __launch_bounds__(256) k_fifo_victims(int64_t capacity, int32_t max_replace, int64_t* ring, const Ctl* ctl,
+                                                      int32_t* __restrict__ victims) {
+    const int32_t i = blockIdx.x * 256 + threadIdx.x;
+    const int32_t m = ctl->m;
+    const int64_t r = *ring;
+    if (i < m) victims[i] = (int32_t)((r + i) % capacity);
+}
+__global__ void k_fifo_advance(int64_t capacity, int64_t* ring, const Ctl* ctl) { *ring = (*ring + ctl->m) % capacity; }
+
+// one wave per replaced entry: maps, score, row copy from the backing store
+__global__ void __launch_bounds__(256) k_insert(CacheState c, int policy, int32_t dim, const float* __restrict__ store,
+                                                const int32_t* __restrict__ new_ids, const int32_t* __restrict__ victims,
+                                                const Ctl* ctl) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (i >= ctl->m) return;
+    const int32_t s = victims[i], id = new_ids[i];
+    if (lane == 0) {
+        const int32_t old = c.id_of[s];
+        if (old >= 0) c.slot_of[old] = -1;
+        c.id_of[s] = id;
+        c.slot_of[id] = s;
+        c.score[s] = policy == TNS_CACHE_LFU ? 1 : 0;
+        if (i == 0) atomicAdd(&c.counters[2], (unsigned long long)ctl->m);
+    }
+    const float* __restrict__ src = store + (int64_t)id * dim;
+    float* __restrict__ dst = c.rows + (int64_t)s * dim;
+    for (int32_t k = lane; k < dim; k += kWave) dst[k] = src[k];
+}
+
+inline unsigned blocks_for(int64_t n, int per = 256) { return (unsigned)std::max<int64_t>(1, (n + per - 1) / per); }
+inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+// exclusive scan of a[0..n) in place; total to *total; sums = scratch for ceil(n/1024) ints
+void scan_i32(int32_t* a, int64_t n, int32_t* sums, int32_t* total, hipStream_t stream) {
+    const int64_t tiles = (n + kScanTile - 1) / kScanTile;
+    if (tiles > 0) hipLaunchKernelGGL(k_scan_tile_sums, dim3((unsigned)tiles), dim3(256), 0, stream, a, n, sums);
+    hipLaunchKernelGGL(k_scan_sums, dim3(1), dim3(1024), 0, stream, sums, tiles, total);
+    if (tiles > 0) hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)tiles), dim3(256), 0, stream, a, n, sums);
+}
+
+}  // namespace
+
+struct tns_cache {
+    tns_cache_config cfg;
+    CacheState st{};
+    int32_t max_replace = 0;
+};
+
+namespace {
+struct Workspace {
+    Ctl* ctl;
+    int32_t *slots, *flag, *new_ids, *victims, *eq, *take, *sums, *dummy_total;
+    size_t bytes;
+};
+Workspace carve(const tns_cache* c, int64_t B, void* base) {
+    Workspace w{};
+    unsigned char* p = static_cast<unsigned char*>(base);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { unsigned char* r = p ? p + off : nullptr; off += align256(bytes); return r; };
+    const int64_t cap = c->cfg.capacity;
+    w.ctl = reinterpret_cast<Ctl*>(take(sizeof(Ctl)));
+    w.slots = reinterpret_cast<int32_t*>(take((size_t)B * 4));
+    w.flag = reinterpret_cast<int32_t*>(take((size_t)B * 4));
+    w.new_ids = reinterpret_cast<int32_t*>(take((size_t)std::max(c->max_replace, 1) * 4));
+    w.victims = reinterpret_cast<int32_t*>(take((size_t)std::max(c->max_replace, 1) * 4));
+    w.eq = reinterpret_cast<int32_t*>(take((size_t)cap * 4));
+    w.take = reinterpret_cast<int32_t*>(take((size_t)cap * 4));
+    w.sums = reinterpret_cast<int32_t*>(take((size_t)(std::max(B, cap) / kScanTile + 2) * 4));
+    w.dummy_total = reinterpret_cast<int32_t*>(take(4));
+    w.bytes = off;
+    return w;
+}
+}  // namespace
+
+extern "C" {
+
+int tns_cache_create(const tns_cache_config* cfg, tns_cache** out) {
+    tns::clear_error();
+    if (!cfg || !out) return fail(TNS_EINVAL, "null config or output pointer");
+    if (cfg->num_ids < 1 || cfg->num_ids > (int64_t)INT32_MAX) return fail(TNS_EINVAL, "num_ids must be in [1, 2^31-1]");
+    if (cfg->capacity < 1 || cfg->capacity > (int64_t)INT32_MAX / 2) return fail(TNS_EINVAL, "capacity must be in [1, 2^30]");
+    if (cfg->dim < 1 || cfg->dim > (1 << 20)) return fail(TNS_EINVAL, "dim must be in [1, 2^20]");
+    if (cfg->policy < 0 || cfg->policy > 2) return fail(TNS_EINVAL, "unknown policy");
+    if (!(cfg->lambda > 0.0f) || cfg->lambda > 1.0f) return fail(TNS_EINVAL, "lambda must be in (0, 1]");
+    if (cfg->device < 0) return fail(TNS_EINVAL, "negative device ordinal");
+    DeviceGuard guard(cfg->device);
+    if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the cache's device");
+    tns_cache* c = new (std::nothrow) tns_cache();
+    if (!c) return fail(TNS_ENOMEM, "host allocation failed");
+    c->cfg = *cfg;
+    c->max_replace = (int32_t)std::floor(cfg->lambda * (float)cfg->capacity);
+    const int64_t N = cfg->num_ids, C = cfg->capacity;
+    struct Alloc { void** p; size_t bytes; };
+    const Alloc allocs[] = {{(void**)&c->st.slot_of, (size_t)N * 4}, {(void**)&c->st.first_idx, (size_t)N * 4},
+                            {(void**)&c->st.id_of, (size_t)C * 4},   {(void**)&c->st.score, (size_t)C * 4},
+                            {(void**)&c->st.touched, (size_t)C * 4}, {(void**)&c->st.rows, (size_t)C * cfg->dim * 4},
+                            {(void**)&c->st.counters, 3 * 8},        {(void**)&c->st.ring, 8}};
+    for (const Alloc& a : allocs) {
+        const hipError_t e = hipMalloc(a.p, a.bytes);
+        if (e != hipSuccess) {
+            tns_cache_destroy(c);
+            return fail_hip(e, "allocating the cache");
+        }
+    }
+    hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(N)), dim3(256), 0, nullptr, c->st.slot_of, N, -1);
+    hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(N)), dim3(256), 0, nullptr, c->st.first_idx, N, kNoIndex);
+    hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(C)), dim3(256), 0, nullptr, c->st.id_of, C, -1);
+    hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(C)), dim3(256), 0, nullptr, c->st.score, C, 0);
+    hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(C)), dim3(256), 0, nullptr, c->st.touched, C, 0);
+    hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(256), 0, nullptr, reinterpret_cast<int32_t*>(c->st.counters), 6, 0);
+    hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(256), 0, nullptr, reinterpret_cast<int32_t*>(c->st.ring), 2, 0);
+    hipError_t e = hipMemsetAsync(c->st.rows, 0, (size_t)C * cfg->dim * 4, nullptr);
+    if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+    if (e != hipSuccess) {
+        tns_cache_destroy(c);
+        return fail_hip(e, "initialising the cache");
+    }
+    *out = c;
+    return TNS_OK;
+}
+
+int tns_cache_workspace(const tns_cache* cache, int64_t B, size_t* bytes) {
+    tns::clear_error();
+    if (!cache || !bytes || B < 0) return fail(TNS_EINVAL, "null cache/pointer or negative B");
+    *bytes = carve(cache, B, nullptr).bytes;
+    return TNS_OK;
+}
+
+int tns_cache_fetch(tns_cache* cache, int64_t B, const int32_t* d_ids, const float* store, float* d_out, uint8_t* d_hit,
+                    void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+    tns::clear_error();
+    if (!cache) return fail(TNS_EINVAL, "null cache");
+    if (B < 0) return fail(TNS_EINVAL, "negative B");
+    if (B == 0) return TNS_OK;
+    if (B > (int64_t)INT32_MAX) return fail(TNS_ESIZE, "more than 2^31-1 ids in one batch");
+    if (!d_ids || !store || !d_out) return fail(TNS_EINVAL, "null ids, store or output");
+    if (!d_workspace) return fail(TNS_EINVAL, "null workspace");
+    if (reinterpret_cast<uintptr_t>(d_workspace) & 255) return fail(TNS_EINVAL, "workspace must be 256-byte aligned");
+    const Workspace w = carve(cache, B, d_workspace);
+    if (workspace_bytes < w.bytes) return fail(TNS_ESIZE, "workspace smaller than tns_cache_workspace()");
+    DeviceGuard guard(cache->cfg.device);
+    if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the cache's device");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const CacheState& st = cache->st;
+    const int policy = cache->cfg.policy;
+    const int32_t dim = cache->cfg.dim;
+    const int64_t C = cache->cfg.capacity, N = cache->cfg.num_ids;
+    const int32_t maxrep = cache->max_replace;
+
+    hipLaunchKernelGGL(k_lookup, dim3(blocks_for(B)), dim3(256), 0, stream, st, policy, N, B, d_ids, w.slots, d_hit, w.ctl);
+    const bool vec4 = dim % 4 == 0 && ((reinterpret_cast<uintptr_t>(store) | reinterpret_cast<uintptr_t>(d_out)) & 15) == 0;
+    if (vec4)
+        hipLaunchKernelGGL(k_gather<4>, dim3(blocks_for(B * (dim / 4))), dim3(256), 0, stream, st.rows, store, dim, B, d_ids,
+                           w.slots, d_out);
+    else
+        hipLaunchKernelGGL(k_gather<1>, dim3(blocks_for(B * dim)), dim3(256), 0, stream, st.rows, store, dim, B, d_ids, w.slots,
+                           d_out);
+    if (policy == TNS_CACHE_LRU) hipLaunchKernelGGL(k_lru_scores, dim3(blocks_for(C)), dim3(256), 0, stream, st.score, st.touched, C);
+    if (maxrep > 0) {
+        // distinct missed ids in order of first occurrence
+        hipLaunchKernelGGL(k_mark_first, dim3(blocks_for(B)), dim3(256), 0, stream, st.first_idx, B, d_ids, w.slots, w.flag);
+        scan_i32(w.flag, B, w.sums, &w.ctl->n_unique, stream);
+        hipLaunchKernelGGL(k_collect_new, dim3(blocks_for(B)), dim3(256), 0, stream, st.first_idx, B, d_ids, w.slots, w.flag,
+                           maxrep, w.new_ids, w.ctl);
+        // victims
+        if (policy == TNS_CACHE_FIFO) {
+            hipLaunchKernelGGL(k_fifo_victims, dim3(blocks_for(maxrep)), dim3(256), 0, stream, C, maxrep, st.ring, w.ctl, w.victims);
+            hipLaunchKernelGGL(k_fifo_advance, dim3(1), dim3(1), 0, stream, C, st.ring, w.ctl);
+        } else {
+            const unsigned hb = (unsigned)std::min<int64_t>(blocks_for(C), 1024);
+            for (int shift = 24; shift >= 0; shift -= 8) {
+                hipLaunchKernelGGL(k_select_hist, dim3(hb), dim3(256), 0, stream, st.score, C, shift, w.ctl);
+                hipLaunchKernelGGL(k_select_digit, dim3(1), dim3(256), 0, stream, shift, w.ctl);
+            }
+            hipLaunchKernelGGL(k_flag_equal, dim3(blocks_for(C)), dim3(256), 0, stream, st.score, C, w.ctl, w.eq);
+            scan_i32(w.eq, C, w.sums, w.dummy_total, stream);
+            hipLaunchKernelGGL(k_flag_take, dim3(blocks_for(C)), dim3(256), 0, stream, st.score, C, w.ctl, w.eq, w.take);
+            scan_i32(w.take, C, w.sums, w.dummy_total, stream);
+            hipLaunchKernelGGL(k_collect_victims, dim3(blocks_for(C)), dim3(256), 0, stream, st.score, C, w.ctl, w.eq, w.take,
+                               w.victims);
+        }
+        hipLaunchKernelGGL(k_insert, dim3(blocks_for(maxrep, 4)), dim3(256), 0, stream, st, policy, dim, store, w.new_ids, w.victims,
+                           w.ctl);
+    }
+    hipLaunchKernelGGL(k_clear_first, dim3(blocks_for(B)), dim3(256), 0, stream, st.first_idx, B, d_ids, w.slots);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(e, "launching the cache kernels");
+    return TNS_OK;
+}
+
+int tns_cache_stats(tns_cache* cache, void* hip_stream, int64_t* hits, int64_t* misses, int64_t* replaced) {
+    tns::clear_error();
+    if (!cache) return fail(TNS_EINVAL, "null cache");
+    DeviceGuard guard(cache->cfg.device);
+    if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the cache's device");
+    unsigned long long h[3];
+    hipError_t e = hipMemcpyAsync(h, cache->st.counters, sizeof(h), hipMemcpyDeviceToHost, static_cast<hipStream_t>(hip_stream));
+    if (e == hipSuccess) e = hipStreamSynchronize(static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail_hip(e, "reading the cache counters");
+    if (hits) *hits = (int64_t)h[0];
+    if (misses) *misses = (int64_t)h[1];
+    if (replaced) *replaced = (int64_t)h[2];
+    return TNS_OK;
+}
+
+int tns_cache_save(tns_cache* cache, void* hip_stream, int32_t* h_id_of, int32_t* h_score, float* h_rows, int64_t* h_ring) {
+    tns::clear_error();
+    if (!cache || !h_id_of || !h_score || !h_rows || !h_ring) return fail(TNS_EINVAL, "null cache or buffer");
+    DeviceGuard guard(cache->cfg.device);
+    if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the cache's device");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const int64_t C = cache->cfg.capacity;
+    hipError_t e = hipMemcpyAsync(h_id_of, cache->st.id_of, (size_t)C * 4, hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(h_score, cache->st.score, (size_t)C * 4, hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(h_rows, cache->st.rows, (size_t)C * cache->cfg.dim * 4, hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(h_ring, cache->st.ring, 8, hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return fail_hip(e, "saving the cache");
+    return TNS_OK;
+}
+
+int tns_cache_restore(tns_cache* cache, void* hip_stream, const int32_t* h_id_of, const int32_t* h_score, const float* h_rows,
+                      int64_t ring) {
+    tns::clear_error();
+    if (!cache || !h_id_of || !h_score || !h_rows) return fail(TNS_EINVAL, "null cache or buffer");
+    const int64_t C = cache->cfg.capacity, N = cache->cfg.num_ids;
+    if (ring < 0 || ring >= C) return fail(TNS_EINVAL, "ring position outside [0, capacity)");
+    for (int64_t s = 0; s < C; ++s)
+        if (h_id_of[s] < -1 || h_id_of[s] >= N) return fail(TNS_ERANGE, "saved id outside [-1, num_ids)");
+    DeviceGuard guard(cache->cfg.device);
+    if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the cache's device");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = hipMemcpyAsync(cache->st.id_of, h_id_of, (size_t)C * 4, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(cache->st.score, h_score, (size_t)C * 4, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(cache->st.rows, h_rows, (size_t)C * cache->cfg.dim * 4, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipMemcpyAsync(cache->st.ring, &ring, 8, hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) return fail_hip(e, "restoring the cache");
+    hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(N)), dim3(256), 0, s, cache->st.slot_of, N, -1);
+    hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(C)), dim3(256), 0, s, cache->st.touched, C, 0);
+    hipLaunchKernelGGL(k_rebuild_map, dim3(blocks_for(C)), dim3(256), 0, s, cache->st.id_of, C, N, cache->st.slot_of);
+    e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return fail_hip(e, "restoring the cache");
+    return TNS_OK;
+}
+
+int tns_cache_destroy(tns_cache* cache) {
+    tns::clear_error();
+    if (!cache) return TNS_OK;
+    {
+        DeviceGuard guard(cache->cfg.device);
+        void* ptrs[] = {cache->st.slot_of, cache->st.first_idx, cache->st.id_of, cache->st.score,
+                        cache->st.touched, cache->st.rows,      cache->st.counters, cache->st.ring};
+        for (void* p : ptrs)
+            if (p) (void)hipFree(p);
+    }
+    delete cache;
+    return TNS_OK;
+}
+
+}  // extern "C"

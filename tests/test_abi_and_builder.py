@@ -19,6 +19,11 @@ def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "tns.h")).read()
     declared = re.findall(r"TNS_API\s+[\w\s\*]+?\b(tns_\w+)\s*\(", hdr)
     assert sorted(declared) == sorted(B.EXPORTS)
+    from paper_2311_17410_amd import cache_binding as KB
+    hdr2 = open(os.path.join(ROOT, "include", "tns_cache.h")).read()
+    declared2 = re.findall(r"TNS_API\s+[\w\s\*]+?\b(tns_\w+)\s*\(", hdr2)
+    assert sorted(declared2) == sorted(KB.EXPORTS)
+    declared = declared + declared2
     L = ctypes.CDLL(B.LIB_PATH)
     for name in declared:
         assert hasattr(L, name), name

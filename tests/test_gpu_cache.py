@@ -1,0 +1,93 @@
+"""GPU parity of the vectorised feature cache against its oracle: returned rows and hit flags,
+and the whole cache state (id per slot, scores, rows, ring) after every batch, bit for bit."""
+import numpy as np
+import pytest
+
+from oracle import cache_oracle as CO
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def KB():
+    import torch
+    assert torch.cuda.is_available()
+    from paper_2311_17410_amd import cache_binding
+    cache_binding.lib()
+    return cache_binding
+
+
+def run_sequence(KB, policy, n, cap, dim, lam, batches, seed, check_state_every=1):
+    import torch
+    dev = torch.device("cuda", 0)
+    store = np.random.default_rng(seed).standard_normal((n, dim)).astype(np.float32)
+    d_store = torch.from_numpy(store).to(dev)
+    ref = CO.VectorCache(n, cap, dim, policy, lam)
+    gpu = KB.Cache(n, cap, dim, policy, lam)
+    for it, ids in enumerate(batches):
+        ids = np.asarray(ids, np.int32)
+        out, hit = gpu.fetch(torch.from_numpy(ids).to(dev), d_store)
+        valid = (ids >= 0) & (ids < n)
+        r_out, r_hit = ref.fetch(ids[valid], store)
+        out, hit = out.cpu().numpy(), hit.cpu().numpy().astype(bool)
+        assert np.array_equal(out[valid].view(np.int32), r_out.view(np.int32)), f"rows, batch {it}"
+        assert np.all(out[~valid] == 0) and not hit[~valid].any()
+        assert np.array_equal(hit[valid], r_hit), f"hit flags, batch {it}"
+        if it % check_state_every == 0 or it == len(batches) - 1:
+            st = gpu.save()
+            assert np.array_equal(st["id_of"], ref.id_of), f"id per slot, batch {it}"
+            occ = ref.id_of >= 0
+            if policy != CO.FIFO:
+                assert np.array_equal(st["score"], ref.score), f"scores, batch {it}"
+            else:
+                assert st["ring"] == ref.ring
+            assert np.array_equal(st["rows"][occ].view(np.int32), ref.data[occ].view(np.int32)), f"cached rows, batch {it}"
+    s = gpu.stats()
+    assert (s["hits"], s["misses"], s["replaced"]) == (ref.hits, ref.misses, ref.replaced)
+    return gpu, ref, store, d_store
+
+
+@pytest.mark.parametrize("policy", [CO.LRU, CO.LFU, CO.FIFO])
+@pytest.mark.parametrize("dim", [4, 7, 172])
+def test_small_batches_every_state(KB, policy, dim):
+    rng = np.random.default_rng(10 + policy)
+    n, cap = 300, 37
+    batches = [(rng.zipf(1.2, int(rng.integers(1, 70))) % n) for _ in range(120)]
+    batches[5] = np.array([-1, 3, n, 3, 2 ** 31 - 1], np.int64)          # ids out of range return zero rows
+    gpu, *_ = run_sequence(KB, policy, n, cap, dim, 0.2, batches, 1)
+    gpu.close()
+
+
+@pytest.mark.parametrize("policy", [CO.LRU, CO.LFU, CO.FIFO])
+def test_large_batches_and_lambda_one(KB, policy):
+    rng = np.random.default_rng(20 + policy)
+    n, cap = 200_000, 5_000
+    batches = [(rng.zipf(1.1, 40_000) % n) for _ in range(8)]
+    gpu, *_ = run_sequence(KB, policy, n, cap, 16, 1.0, batches, 2)
+    gpu.close()
+    batches = [(rng.zipf(1.1, 30_000) % n) for _ in range(8)]
+    gpu, *_ = run_sequence(KB, policy, n, cap, 16, 0.2, batches, 3)
+    gpu.close()
+
+
+def test_paper_scale_shapes_and_restore(KB):
+    import torch
+    # edge-feature shaped rows (172 floats), cache of 1 % of the ids, batches of "thousands" (section 4.3)
+    rng = np.random.default_rng(30)
+    n, cap = 1_000_000, 10_000
+    batches = [(rng.zipf(1.05, 60_000) % n) for _ in range(6)]
+    gpu, ref, store, d_store = run_sequence(KB, CO.LRU, n, cap, 172, 0.2, batches, 4, check_state_every=3)
+    # restoration (section 4.3): save at the start of a round, pollute, restore: same state as saved
+    saved = gpu.save()
+    dev = torch.device("cuda", 0)
+    for _ in range(3):
+        gpu.fetch(torch.from_numpy((rng.integers(0, n, 50_000)).astype(np.int32)).to(dev), d_store)
+    gpu.restore(saved)
+    again = gpu.save()
+    for k in ("id_of", "score", "rows"):
+        assert np.array_equal(again[k], saved[k])
+    ids = (rng.zipf(1.05, 20_000) % n).astype(np.int32)
+    out, hit = gpu.fetch(torch.from_numpy(ids).to(dev), d_store)
+    r_out, r_hit = ref.fetch(ids, store)
+    assert np.array_equal(out.cpu().numpy(), r_out) and np.array_equal(hit.cpu().numpy().astype(bool), r_hit)
+    gpu.close()

@@ -22,6 +22,7 @@ namespace {
 constexpr int kWave = 64;
 constexpr int kScanTile = 1024;           // elements per workgroup in the scans
 constexpr int kNoIndex = INT_MAX;
+constexpr int kStripes = 64;
 
 // Device-side scalars of one fetch.
 struct Ctl {
@@ -39,7 +40,7 @@ struct CacheState {
     int32_t* score;      // [capacity]  recent score (LRU) / access count (LFU)
     int32_t* touched;    // [capacity]  LRU: accessed by the current batch
     float* rows;         // [capacity * dim]
-    unsigned long long* counters;  // hits, misses, replaced
+    unsigned long long* counters;  // [kStripes][3]: hits, misses, replaced (striped: one hot word would serialise the batch)
     int64_t* ring;       // FIFO position
 };
 
@@ -87,8 +88,9 @@ __global__ void __launch_bounds__(256) k_lookup(CacheState c, int policy, int64_
     }
     const unsigned long long h = __popcll(__ballot(is_hit)), m = __popcll(__ballot(is_miss));
     if ((threadIdx.x & (kWave - 1)) == 0) {
-        if (h) atomicAdd(&c.counters[0], h);
-        if (m) atomicAdd(&c.counters[1], m);
+        unsigned long long* mine = c.counters + (size_t)((blockIdx.x * 4 + (threadIdx.x >> 6)) % kStripes) * 3;
+        if (h) atomicAdd(&mine[0], h);
+        if (m) atomicAdd(&mine[1], m);
     }
 }
 
@@ -400,7 +402,7 @@ int tns_cache_create(const tns_cache_config* cfg, tns_cache** out) {
     const Alloc allocs[] = {{(void**)&c->st.slot_of, (size_t)N * 4}, {(void**)&c->st.first_idx, (size_t)N * 4},
                             {(void**)&c->st.id_of, (size_t)C * 4},   {(void**)&c->st.score, (size_t)C * 4},
                             {(void**)&c->st.touched, (size_t)C * 4}, {(void**)&c->st.rows, (size_t)C * cfg->dim * 4},
-                            {(void**)&c->st.counters, 3 * 8},        {(void**)&c->st.ring, 8}};
+                            {(void**)&c->st.counters, kStripes * 3 * 8},        {(void**)&c->st.ring, 8}};
     for (const Alloc& a : allocs) {
         const hipError_t e = hipMalloc(a.p, a.bytes);
         if (e != hipSuccess) {
@@ -413,7 +415,7 @@ int tns_cache_create(const tns_cache_config* cfg, tns_cache** out) {
     hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(C)), dim3(256), 0, nullptr, c->st.id_of, C, -1);
     hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(C)), dim3(256), 0, nullptr, c->st.score, C, 0);
     hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(C)), dim3(256), 0, nullptr, c->st.touched, C, 0);
-    hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(256), 0, nullptr, reinterpret_cast<int32_t*>(c->st.counters), 6, 0);
+    hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(kStripes * 6)), dim3(256), 0, nullptr, reinterpret_cast<int32_t*>(c->st.counters), kStripes * 6, 0);
     hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(256), 0, nullptr, reinterpret_cast<int32_t*>(c->st.ring), 2, 0);
     hipError_t e = hipMemsetAsync(c->st.rows, 0, (size_t)C * cfg->dim * 4, nullptr);
     if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
@@ -499,10 +501,12 @@ int tns_cache_stats(tns_cache* cache, void* hip_stream, int64_t* hits, int64_t* 
     if (!cache) return fail(TNS_EINVAL, "null cache");
     DeviceGuard guard(cache->cfg.device);
     if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the cache's device");
-    unsigned long long h[3];
-    hipError_t e = hipMemcpyAsync(h, cache->st.counters, sizeof(h), hipMemcpyDeviceToHost, static_cast<hipStream_t>(hip_stream));
+    unsigned long long all[kStripes * 3], h[3] = {0, 0, 0};
+    hipError_t e = hipMemcpyAsync(all, cache->st.counters, sizeof(all), hipMemcpyDeviceToHost, static_cast<hipStream_t>(hip_stream));
     if (e == hipSuccess) e = hipStreamSynchronize(static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail_hip(e, "reading the cache counters");
+    for (int i = 0; i < kStripes; ++i)
+        for (int k = 0; k < 3; ++k) h[k] += all[i * 3 + k];
     if (hits) *hits = (int64_t)h[0];
     if (misses) *misses = (int64_t)h[1];
     if (replaced) *replaced = (int64_t)h[2];

@@ -85,6 +85,9 @@ def main() -> int:
     ap.add_argument("--policy", default="recent", choices=["recent", "uniform"])
     ap.add_argument("--windowed", action="store_true", help="t_start = t_end - 0.25 span instead of -inf")
     ap.add_argument("--no-remap", action="store_true", help="disable the XCD-aware tile mapping")
+    ap.add_argument("--placement", default="hbm", choices=["hbm", "hybrid", "host"],
+                    help="hbm: the whole store in device memory (default); hybrid: edge data in page-locked host "
+                         "memory, metadata on the device (the paper's placement); host: everything in host memory")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (torch copy_) so that rocprofv3 counter runs of this "
                          "command contain a kernel of known traffic")
@@ -117,7 +120,9 @@ def main() -> int:
     log(f"ingesting {Q} edges into {wl.num_instances} instance(s), tau={wl.tau}")
     t0 = time.time()
     plan = B.Plan(wl.num_nodes, f, policy=policy, block_threshold=wl.tau, num_instances=wl.num_instances,
-                  seed=wl.seed, flags=B.TNS_FLAG_NO_XCD_REMAP if args.no_remap else 0)
+                  seed=wl.seed,
+                  flags=(B.TNS_FLAG_NO_XCD_REMAP if args.no_remap else 0)
+                  | {"hbm": 0, "hybrid": B.TNS_FLAG_EDGES_ON_HOST, "host": B.TNS_FLAG_ALL_ON_HOST}[args.placement])
     last = time.time()
     for i, st in enumerate(wl.streams):
         for lo, hi in st.batches():
@@ -222,10 +227,11 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.description}; query i = (src[i], -inf, ts[i]); f={f}, tau={wl.tau}, "
                                f"policy={args.policy}, window={'0.25 span' if args.windowed else 'unbounded'}",
-                   "queries": Q, "instances": wl.num_instances, "nodes_per_instance": wl.num_nodes},
+                   "queries": Q, "instances": wl.num_instances, "nodes_per_instance": wl.num_nodes,
+                   "placement": args.placement},
         "roofline": {"bound": "hbm", "kernel": "tns_sample_kernel (padding removal fused)" if args.policy == "recent" else "tns_sample_kernel + tns_compact kernels (whole step)", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": measured_traffic(wl.name, args.policy),
+                     "traffic": measured_traffic(wl.name, args.policy) if args.placement == "hbm" else None,
                      "algorithmic_bytes_per_launch": alg_step, "bytes_breakdown": bytes_step,
                      "ms_per_launch": ms_kernel},
         "two_kernel_path": {"sample_ms": ms_sample, "sample_GBs": alg_sample / (ms_sample * 1e-3) / 1e9,

@@ -58,9 +58,16 @@ enum { TNS_MAX_FANOUT = 64 };
 /* tns_config.flags */
 enum {
     TNS_FLAG_NO_XCD_REMAP = 1, /* keep the hardware's round-robin workgroup->XCD order (for measurements) */
-    TNS_FLAG_NO_NODE_SLAB = 2  /* do not reserve one 128-byte edge line per non-empty node for its first
+    TNS_FLAG_NO_NODE_SLAB = 2, /* do not reserve one 128-byte edge line per non-empty node for its first
                                   blocks: less memory for graphs of mostly degree-1 nodes, more lines
                                   read per query                                                        */
+    /* Placement (section 4.1, "hybrid GPU-CPU graph data placement").  Default: node table, block
+       records and edge data all in device memory.  EDGES_ON_HOST is the paper's hybrid placement:
+       the metadata (node table, block records) in device memory, the edge data in page-locked host
+       memory that the kernels read across the host link.  ALL_ON_HOST puts the metadata there too
+       (the paper's "UVA-only" comparison point).  Results are identical under all three. */
+    TNS_FLAG_EDGES_ON_HOST = 4,
+    TNS_FLAG_ALL_ON_HOST = 8
 };
 
 typedef struct {

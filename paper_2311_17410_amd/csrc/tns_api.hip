@@ -42,6 +42,18 @@ struct DeviceArray {
     T* ptr = nullptr;
     int64_t cap = 0;   // elements allocated
     int64_t used = 0;  // elements valid on the device
+    bool on_host = false;   // page-locked host memory the device reads directly, instead of device memory
+
+    hipError_t alloc(T** p, int64_t n) const {
+        const size_t bytes = (size_t)n * sizeof(T);
+        return on_host ? hipHostMalloc(reinterpret_cast<void**>(p), bytes, hipHostMallocMapped | hipHostMallocPortable)
+                       : hipMalloc(reinterpret_cast<void**>(p), bytes);
+    }
+    void release() {
+        if (ptr) (void)(on_host ? hipHostFree(ptr) : hipFree(ptr));
+        ptr = nullptr;
+        cap = used = 0;
+    }
 };
 
 }  // namespace
@@ -64,13 +76,14 @@ int ensure_capacity(DeviceArray<T>& d, int64_t need, P& host, const char* what) 
     if (need <= d.cap) return TNS_OK;
     int64_t cap = need + need / 4 + 1024;
     T* p = nullptr;
-    hipError_t e = hipMalloc(reinterpret_cast<void**>(&p), (size_t)cap * sizeof(T));
+    hipError_t e = d.alloc(&p, cap);
     if (e != hipSuccess) {
+        (void)hipGetLastError();
         cap = need;
-        e = hipMalloc(reinterpret_cast<void**>(&p), (size_t)cap * sizeof(T));
+        e = d.alloc(&p, cap);
     }
     if (e != hipSuccess) return fail_hip(e, what);
-    if (d.ptr) (void)hipFree(d.ptr);
+    d.release();
     d.ptr = p;
     d.cap = cap;
     d.used = 0;
@@ -83,7 +96,7 @@ int upload_dirty(DeviceArray<T>& d, const P& host, hipStream_t stream, const cha
     hipError_t first = hipSuccess;
     host.for_each_dirty([&](int64_t start, int64_t count, const T* src) {
         if (first != hipSuccess) return;
-        first = hipMemcpyAsync(d.ptr + start, src, (size_t)count * sizeof(T), hipMemcpyHostToDevice, stream);
+        first = hipMemcpyAsync(d.ptr + start, src, (size_t)count * sizeof(T), hipMemcpyDefault, stream);
     });
     if (first != hipSuccess) return fail_hip(first, what);
     d.used = host.size();
@@ -105,9 +118,15 @@ int tns_plan_create(const tns_config* cfg, tns_plan** out) {
     if (cfg->sizing < 0 || cfg->sizing > 2) return fail(TNS_EINVAL, "unknown sizing method");
     if (cfg->inclusive_end != 0 && cfg->inclusive_end != 1) return fail(TNS_EINVAL, "inclusive_end must be 0 or 1");
     if (cfg->device < 0) return fail(TNS_EINVAL, "negative device ordinal");
+    constexpr int32_t kKnownFlags = TNS_FLAG_NO_XCD_REMAP | TNS_FLAG_NO_NODE_SLAB | TNS_FLAG_EDGES_ON_HOST | TNS_FLAG_ALL_ON_HOST;
+    if (cfg->flags & ~kKnownFlags) return fail(TNS_EINVAL, "unknown bit in flags");
+    if ((cfg->flags & TNS_FLAG_EDGES_ON_HOST) && (cfg->flags & TNS_FLAG_ALL_ON_HOST))
+        return fail(TNS_EINVAL, "TNS_FLAG_EDGES_ON_HOST and TNS_FLAG_ALL_ON_HOST exclude each other");
     try {
         std::unique_ptr<tns_plan> p(new tns_plan());
         p->cfg = *cfg;
+        p->d_edges.on_host = (cfg->flags & (TNS_FLAG_EDGES_ON_HOST | TNS_FLAG_ALL_ON_HOST)) != 0;
+        p->d_nodes.on_host = p->d_dir.on_host = (cfg->flags & TNS_FLAG_ALL_ON_HOST) != 0;
         tns::StoreConfig sc;
         sc.num_nodes = cfg->num_nodes;
         sc.num_instances = cfg->num_instances;
@@ -511,9 +530,9 @@ int tns_destroy(tns_plan* plan) {
     if (!plan) return TNS_OK;
     if (plan->d_nodes.ptr || plan->d_dir.ptr || plan->d_edges.ptr) {
         DeviceGuard guard(plan->cfg.device);
-        if (plan->d_nodes.ptr) (void)hipFree(plan->d_nodes.ptr);
-        if (plan->d_dir.ptr) (void)hipFree(plan->d_dir.ptr);
-        if (plan->d_edges.ptr) (void)hipFree(plan->d_edges.ptr);
+        plan->d_nodes.release();
+        plan->d_dir.release();
+        plan->d_edges.release();
     }
     delete plan;
     return TNS_OK;

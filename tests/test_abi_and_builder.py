@@ -40,7 +40,9 @@ def test_argument_validation():
                        (dict(num_nodes=4, fanout=3, block_threshold=0), B.TNS_EINVAL),
                        (dict(num_nodes=4, fanout=3, num_instances=0), B.TNS_EINVAL),
                        (dict(num_nodes=4, fanout=3, sizing=3), B.TNS_EINVAL),
-                       (dict(num_nodes=4, fanout=3, inclusive_end=2), B.TNS_EINVAL)]:
+                       (dict(num_nodes=4, fanout=3, inclusive_end=2), B.TNS_EINVAL),
+                       (dict(num_nodes=4, fanout=3, flags=16), B.TNS_EINVAL),
+                       (dict(num_nodes=4, fanout=3, flags=B.TNS_FLAG_EDGES_ON_HOST | B.TNS_FLAG_ALL_ON_HOST), B.TNS_EINVAL)]:
         with pytest.raises(B.TnsError) as ei:
             B.tns_plan_create(**kw)
         assert ei.value.status == status

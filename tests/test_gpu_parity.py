@@ -323,6 +323,27 @@ def test_c2_inclusive_and_no_remap(B, oracle_lib):
         plan.close()
 
 
+@pytest.mark.parametrize("policy", [0, 1])
+def test_host_placement_gives_the_same_results(B, oracle_lib, policy):
+    # section 4.1: edge data in page-locked host memory with the metadata on the device (hybrid),
+    # or everything in host memory; also a second commit after more edges (the arrays grow)
+    wl = W.c2()
+    st = wl.streams[0]
+    targets, t_start, t_end, _ = wl.queries(window_frac=0.25)
+    ref = oracle_sample(oracle_lib, wl, targets, t_start, t_end, None, wl.fanout, policy, 0, 5, threads=16)
+    for flags in (B.TNS_FLAG_EDGES_ON_HOST, B.TNS_FLAG_ALL_ON_HOST):
+        plan = B.Plan(wl.num_nodes, wl.fanout, policy=policy, block_threshold=wl.tau, seed=5, flags=flags)
+        half = st.n // 2
+        for lo, hi in ((0, half), (half, st.n)):
+            for a in range(lo, hi, st.batch):
+                b = min(a + st.batch, hi)
+                plan.add_edges(st.src[a:b], st.dst[a:b], st.ts[a:b])
+            plan.commit()
+        got = gpu_sample(plan, targets, t_start, t_end)
+        assert_same(got, ref, oracle_lib, f"policy={policy} flags={flags}")
+        plan.close()
+
+
 def test_c3_zipf_hub(B, oracle_lib):
     progress("generating C3")
     _check_config(B, oracle_lib, W.c3())

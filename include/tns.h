@@ -67,7 +67,12 @@ enum {
        memory that the kernels read across the host link.  ALL_ON_HOST puts the metadata there too
        (the paper's "UVA-only" comparison point).  Results are identical under all three. */
     TNS_FLAG_EDGES_ON_HOST = 4,
-    TNS_FLAG_ALL_ON_HOST = 8
+    TNS_FLAG_ALL_ON_HOST = 8,
+    /* The store is built on the device: batches come from device memory through
+       tns_add_edges_device and are visible to the next tns_run on the same stream; there is no
+       host copy, tns_add_edges is refused (TNS_ESTATE) and tns_commit has nothing to upload.
+       Cannot be combined with the host placements or TNS_FLAG_NO_NODE_SLAB. */
+    TNS_FLAG_DEVICE_INGEST = 16
 };
 
 typedef struct {
@@ -112,6 +117,19 @@ TNS_API int tns_set_sampler(tns_plan *plan, int32_t fanout, int32_t policy, int3
  */
 TNS_API int tns_add_edges(tns_plan *plan, int32_t instance, const int32_t *src, const int32_t *dst,
                   const float *ts, const int32_t *eid, int64_t m);
+
+/*
+ * The same insertion (section 4.1) for a plan created with TNS_FLAG_DEVICE_INGEST, run on the GPU:
+ * all arrays are DEVICE, length m <= 2^24-1, d_eid may be NULL.  The batch is sorted by (source,
+ * time, arrival) on the device, every source node's share is appended to its tail block and, if
+ * edges remain, to new blocks sized by the same rule as tns_add_edges; block capacities, sizes and
+ * time ranges per node are identical to the host builder's, only where the blocks lie in the edge
+ * array differs.  Same status codes; a rejected batch changes nothing.  The call grows the
+ * device pools when needed (it may allocate), waits for the stream, and returns when the batch
+ * is stored: a later tns_run on any stream sees it.  No tns_commit is needed.
+ */
+TNS_API int tns_add_edges_device(tns_plan *plan, int32_t instance, const int32_t *d_src, const int32_t *d_dst,
+                                 const float *d_ts, const int32_t *d_eid, int64_t m, void *hip_stream);
 
 /*
  * Tombstone deletion (section 4.1: validity fields are cleared while data layouts and pointers

@@ -23,8 +23,9 @@ TNS_FLAG_NO_XCD_REMAP = 1
 TNS_FLAG_NO_NODE_SLAB = 2
 TNS_FLAG_EDGES_ON_HOST = 4
 TNS_FLAG_ALL_ON_HOST = 8
+TNS_FLAG_DEVICE_INGEST = 16
 
-EXPORTS = ["tns_plan_create", "tns_set_sampler", "tns_add_edges", "tns_delete_edges", "tns_delete_nodes", "tns_commit", "tns_workspace", "tns_run", "tns_workspace_khop", "tns_run_khop", "tns_compact", "tns_traffic_model", "tns_stats",
+EXPORTS = ["tns_plan_create", "tns_set_sampler", "tns_add_edges", "tns_add_edges_device", "tns_delete_edges", "tns_delete_nodes", "tns_commit", "tns_workspace", "tns_run", "tns_workspace_khop", "tns_run_khop", "tns_compact", "tns_traffic_model", "tns_stats",
            "tns_node_blocks", "tns_destroy", "tns_strerror", "tns_last_error"]
 
 
@@ -70,6 +71,8 @@ def lib():
         L.tns_set_sampler.restype = C.c_int
         L.tns_add_edges.argtypes = [vp, C.c_int32, i32p, i32p, f32p, i32p, C.c_int64]
         L.tns_add_edges.restype = C.c_int
+        L.tns_add_edges_device.argtypes = [vp, C.c_int32, vp, vp, vp, vp, C.c_int64, vp]
+        L.tns_add_edges_device.restype = C.c_int
         L.tns_delete_edges.argtypes = [vp, C.c_int32, i32p, i32p, C.c_int64, i64p]
         L.tns_delete_edges.restype = C.c_int
         L.tns_delete_nodes.argtypes = [vp, C.c_int32, i32p, C.c_int64, C.c_int32]
@@ -140,6 +143,12 @@ def tns_add_edges(plan, instance: int, src, dst, ts, eid=None) -> None:
     if not (len(src_a) == len(dst_a) == len(ts_a)) or (eid_a is not None and len(eid_a) != len(src_a)):
         raise ValueError("src, dst, ts (and eid) must have the same length")
     _check(lib().tns_add_edges(plan, instance, src_p, dst_p, ts_p, eid_p, len(src_a)), "tns_add_edges")
+
+
+def tns_add_edges_device(plan, instance: int, d_src: int, d_dst: int, d_ts: int, d_eid: Optional[int], m: int,
+                         stream: int) -> None:
+    """Raw device pointers (ints) of the batch arrays; d_eid may be None."""
+    _check(lib().tns_add_edges_device(plan, instance, d_src, d_dst, d_ts, d_eid, m, stream), "tns_add_edges_device")
 
 
 def tns_delete_edges(plan, instance: int, src, eid) -> int:
@@ -263,6 +272,21 @@ class Plan:
 
     def add_edges(self, src, dst, ts, eid=None, instance: int = 0):
         tns_add_edges(self._h, instance, src, dst, ts, eid)
+
+    def add_edges_device(self, src, dst, ts, eid=None, instance: int = 0):
+        """Batch given as torch tensors on the plan's device (int32, int32, float32[, int32]); needs a plan
+        created with TNS_FLAG_DEVICE_INGEST."""
+        import torch
+        want = [(src, torch.int32), (dst, torch.int32), (ts, torch.float32)] + ([(eid, torch.int32)] if eid is not None else [])
+        for t, dt in want:
+            if t.dtype != dt or not t.is_cuda or t.device.index != self.device or not t.is_contiguous() or t.dim() != 1:
+                raise ValueError("batch arrays must be contiguous 1-d tensors of the right dtype on the plan's device")
+            if t.numel() != src.numel():
+                raise ValueError("src, dst, ts (and eid) must have the same length")
+        with torch.cuda.device(self.device):
+            tns_add_edges_device(self._h, instance, src.data_ptr(), dst.data_ptr(), ts.data_ptr(),
+                                 None if eid is None else eid.data_ptr(), src.numel(),
+                                 torch.cuda.current_stream().cuda_stream)
 
     def add_stream(self, stream, instance: int = 0):
         """Ingest a workloads.Stream batch by batch, as the paper's continuous-learning setting does."""

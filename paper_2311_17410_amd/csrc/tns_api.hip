@@ -8,8 +8,10 @@
 #include <memory>
 #include <new>
 #include <string>
+#include <vector>
 
 #include "../../include/tns.h"
+#include "tns_ingest.h"
 #include "tns_internal.h"
 #include "tns_kernels.h"
 #include "tns_store.h"
@@ -56,11 +58,20 @@ struct DeviceArray {
     }
 };
 
+// State of a plan whose store is built on the device (TNS_FLAG_DEVICE_INGEST): no host copy.
+struct DeviceStore {
+    DeviceArray<tns::NodeAux> aux;
+    DeviceArray<unsigned char> ws;              // scratch of the ingestion kernels, grown on demand
+    tns::IngestStatus* d_status = nullptr;
+    std::vector<tns::InstanceTotals> totals;   // per instance: edges, blocks, slots, running edge id, deleted
+};
+
 }  // namespace
 
 struct tns_plan {
     tns_config cfg;
-    std::unique_ptr<tns::Store> store;
+    std::unique_ptr<tns::Store> store;          // host builder (null for a device-built store)
+    std::unique_ptr<DeviceStore> dev;           // device builder (null otherwise)
     DeviceArray<tns::NodeLine> d_nodes;
     DeviceArray<tns::BlockRec> d_dir;
     DeviceArray<tns::EdgeLine> d_edges;
@@ -103,6 +114,80 @@ int upload_dirty(DeviceArray<T>& d, const P& host, hipStream_t stream, const cha
     return TNS_OK;
 }
 
+// Device-built store: room for `need` elements, keeping the first `used` ones (device-to-device copy).
+template <class T>
+int grow_device(DeviceArray<T>& d, int64_t need, hipStream_t stream, const char* what) {
+    if (need <= d.cap) return TNS_OK;
+    int64_t cap = need + need / 2 + 1024;
+    T* p = nullptr;
+    hipError_t e = d.alloc(&p, cap);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        cap = need;
+        e = d.alloc(&p, cap);
+    }
+    if (e != hipSuccess) return fail_hip(e, what);
+    if (d.ptr && d.used > 0) {
+        e = hipMemcpyAsync(p, d.ptr, (size_t)d.used * sizeof(T), hipMemcpyDeviceToDevice, stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(stream);
+        if (e != hipSuccess) {
+            (void)hipFree(p);
+            return fail_hip(e, what);
+        }
+    }
+    const int64_t used = d.used;
+    d.release();
+    d.ptr = p;
+    d.cap = cap;
+    d.used = used;
+    return TNS_OK;
+}
+
+// Device-built store: first use allocates the (empty) node table, the builder state and the status record.
+int ensure_device_store(tns_plan* plan, hipStream_t stream) {
+    DeviceStore& ds = *plan->dev;
+    if (ds.d_status) return TNS_OK;
+    const int64_t total_nodes = std::max<int64_t>((int64_t)plan->cfg.num_instances * plan->cfg.num_nodes, 1);
+    int rc;
+    if ((rc = grow_device(plan->d_nodes, total_nodes, stream, "allocating node table"))) return rc;
+    if ((rc = grow_device(ds.aux, total_nodes, stream, "allocating the builder state"))) return rc;
+    if ((rc = grow_device(plan->d_dir, 1024, stream, "allocating the block directory"))) return rc;
+    if ((rc = grow_device(plan->d_edges, 1024, stream, "allocating edge data"))) return rc;
+    hipError_t e = hipMemsetAsync(plan->d_nodes.ptr, 0, (size_t)total_nodes * sizeof(tns::NodeLine), stream);
+    if (e == hipSuccess) e = hipMemsetAsync(ds.aux.ptr, 0, (size_t)total_nodes * sizeof(tns::NodeAux), stream);
+    tns::IngestStatus* st = nullptr;
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&st), sizeof(tns::IngestStatus));
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) {
+        if (st) (void)hipFree(st);
+        return fail_hip(e, "initialising the device store");
+    }
+    plan->d_nodes.used = total_nodes;
+    ds.aux.used = total_nodes;
+    ds.d_status = st;
+    plan->committed = true;
+    return TNS_OK;
+}
+
+int read_status(tns_plan* plan, hipStream_t stream, tns::IngestStatus& out, const char* what) {
+    hipError_t e = hipMemcpyAsync(&out, plan->dev->d_status, sizeof(out), hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return fail_hip(e, what);
+    return TNS_OK;
+}
+
+// Copies a host array into a temporary device buffer (deletion requests).
+template <class T>
+struct DeviceTemp {
+    T* ptr = nullptr;
+    ~DeviceTemp() { if (ptr) (void)hipFree(ptr); }
+    hipError_t upload(const T* host, int64_t n, hipStream_t stream) {
+        hipError_t e = hipMalloc(reinterpret_cast<void**>(&ptr), (size_t)std::max<int64_t>(n, 1) * sizeof(T));
+        if (e == hipSuccess && n > 0) e = hipMemcpyAsync(ptr, host, (size_t)n * sizeof(T), hipMemcpyHostToDevice, stream);
+        return e;
+    }
+};
+
 }  // namespace
 
 extern "C" {
@@ -118,22 +203,31 @@ int tns_plan_create(const tns_config* cfg, tns_plan** out) {
     if (cfg->sizing < 0 || cfg->sizing > 2) return fail(TNS_EINVAL, "unknown sizing method");
     if (cfg->inclusive_end != 0 && cfg->inclusive_end != 1) return fail(TNS_EINVAL, "inclusive_end must be 0 or 1");
     if (cfg->device < 0) return fail(TNS_EINVAL, "negative device ordinal");
-    constexpr int32_t kKnownFlags = TNS_FLAG_NO_XCD_REMAP | TNS_FLAG_NO_NODE_SLAB | TNS_FLAG_EDGES_ON_HOST | TNS_FLAG_ALL_ON_HOST;
+    constexpr int32_t kKnownFlags = TNS_FLAG_NO_XCD_REMAP | TNS_FLAG_NO_NODE_SLAB | TNS_FLAG_EDGES_ON_HOST |
+                                    TNS_FLAG_ALL_ON_HOST | TNS_FLAG_DEVICE_INGEST;
     if (cfg->flags & ~kKnownFlags) return fail(TNS_EINVAL, "unknown bit in flags");
     if ((cfg->flags & TNS_FLAG_EDGES_ON_HOST) && (cfg->flags & TNS_FLAG_ALL_ON_HOST))
         return fail(TNS_EINVAL, "TNS_FLAG_EDGES_ON_HOST and TNS_FLAG_ALL_ON_HOST exclude each other");
+    if ((cfg->flags & TNS_FLAG_DEVICE_INGEST) &&
+        (cfg->flags & (TNS_FLAG_EDGES_ON_HOST | TNS_FLAG_ALL_ON_HOST | TNS_FLAG_NO_NODE_SLAB)))
+        return fail(TNS_EINVAL, "TNS_FLAG_DEVICE_INGEST cannot be combined with host placement or TNS_FLAG_NO_NODE_SLAB");
     try {
         std::unique_ptr<tns_plan> p(new tns_plan());
         p->cfg = *cfg;
         p->d_edges.on_host = (cfg->flags & (TNS_FLAG_EDGES_ON_HOST | TNS_FLAG_ALL_ON_HOST)) != 0;
         p->d_nodes.on_host = p->d_dir.on_host = (cfg->flags & TNS_FLAG_ALL_ON_HOST) != 0;
-        tns::StoreConfig sc;
-        sc.num_nodes = cfg->num_nodes;
-        sc.num_instances = cfg->num_instances;
-        sc.tau = cfg->block_threshold;
-        sc.sizing = cfg->sizing;
-        sc.node_slab = !(cfg->flags & TNS_FLAG_NO_NODE_SLAB);
-        p->store.reset(new tns::Store(sc));
+        if (cfg->flags & TNS_FLAG_DEVICE_INGEST) {
+            p->dev.reset(new DeviceStore());
+            p->dev->totals.resize((size_t)cfg->num_instances);
+        } else {
+            tns::StoreConfig sc;
+            sc.num_nodes = cfg->num_nodes;
+            sc.num_instances = cfg->num_instances;
+            sc.tau = cfg->block_threshold;
+            sc.sizing = cfg->sizing;
+            sc.node_slab = !(cfg->flags & TNS_FLAG_NO_NODE_SLAB);
+            p->store.reset(new tns::Store(sc));
+        }
         *out = p.release();
     } catch (const std::bad_alloc&) {
         return fail(TNS_ENOMEM, "host allocation failed");
@@ -158,6 +252,7 @@ int tns_add_edges(tns_plan* plan, int32_t instance, const int32_t* src, const in
                   const int32_t* eid, int64_t m) {
     g_err.clear();
     if (!plan) return fail(TNS_EINVAL, "null plan");
+    if (plan->dev) return fail(TNS_ESTATE, "this plan's store is built on the device: use tns_add_edges_device");
     try {
         std::string err;
         const int rc = plan->store->add_edges(instance, src, dst, ts, eid, m, err);
@@ -168,17 +263,126 @@ int tns_add_edges(tns_plan* plan, int32_t instance, const int32_t* src, const in
     }
 }
 
+int tns_add_edges_device(tns_plan* plan, int32_t instance, const int32_t* d_src, const int32_t* d_dst, const float* d_ts,
+                         const int32_t* d_eid, int64_t m, void* hip_stream) {
+    g_err.clear();
+    if (!plan) return fail(TNS_EINVAL, "null plan");
+    if (!plan->dev) return fail(TNS_ESTATE, "tns_add_edges_device needs a plan created with TNS_FLAG_DEVICE_INGEST");
+    if (instance < 0 || instance >= plan->cfg.num_instances) return fail(TNS_ERANGE, "instance out of range");
+    if (m < 0 || (m > 0 && (!d_src || !d_dst || !d_ts))) return fail(TNS_EINVAL, "null array or negative batch size");
+    if (m == 0) return TNS_OK;
+    if (m > tns::kMaxDeviceBatch) return fail(TNS_ESIZE, "batch larger than 2^24-1 edges: split it");
+    DeviceStore& ds = *plan->dev;
+    tns::InstanceTotals& tot = ds.totals[(size_t)instance];
+    if (!d_eid && tot.next_eid + m > (int64_t)INT32_MAX) return fail(TNS_ESIZE, "running edge id would exceed 2^31-1");
+
+    DeviceGuard guard(plan->cfg.device);
+    if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the plan's device");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    int rc;
+    if ((rc = ensure_device_store(plan, stream))) return rc;
+    const int64_t ws_need = (int64_t)tns::ingest_workspace_bytes(m);
+    if (ws_need > ds.ws.cap) {
+        ds.ws.used = 0;   // scratch: nothing to keep
+        if ((rc = grow_device(ds.ws, ws_need, stream, "allocating the ingestion workspace"))) return rc;
+    }
+
+    tns::IngestArgs a{};
+    a.src = d_src;
+    a.dst = d_dst;
+    a.ts = d_ts;
+    a.eid = d_eid;
+    a.m = m;
+    a.eid_base = tot.next_eid;
+    a.nodes = plan->d_nodes.ptr;
+    a.aux = ds.aux.ptr;
+    a.dir = plan->d_dir.ptr;
+    a.lines = reinterpret_cast<uint32_t*>(plan->d_edges.ptr);
+    a.node_base = (int64_t)instance * plan->cfg.num_nodes;
+    a.num_nodes = plan->cfg.num_nodes;
+    a.used_lines = plan->d_edges.used;
+    a.cap_lines = plan->d_edges.cap;
+    a.used_dir = plan->d_dir.used;
+    a.cap_dir = plan->d_dir.cap;
+    a.tau = plan->cfg.block_threshold;
+    a.sizing = plan->cfg.sizing;
+    a.workspace = ds.ws.ptr;
+    a.status = ds.d_status;
+
+    hipError_t e = tns::ingest_plan(a, stream);
+    if (e != hipSuccess) return fail_hip(e, "launching the ingestion planning kernels");
+    tns::IngestStatus st;
+    if ((rc = read_status(plan, stream, st, "waiting for the ingestion plan"))) return rc;
+    if (st.err_word != ~0ull) {
+        const int code = -(int)(st.err_word & 0xffu);
+        const int64_t pos = (int64_t)(st.err_word >> 8);
+        switch (code) {
+            case TNS_ERANGE: return fail(code, "source node id outside [0, num_nodes) at batch position " + std::to_string(pos));
+            case TNS_EINVAL: return fail(code, "negative edge id at batch position " + std::to_string(pos));
+            case TNS_EORDER:
+                if (pos < m) return fail(code, "NaN timestamp at batch position " + std::to_string(pos));
+                return fail(code, "node " + std::to_string(pos - m) + " would receive an edge older than its newest stored edge");
+            default: return fail(TNS_EHIP, "unexpected status from the ingestion kernels");
+        }
+    }
+    if (st.num_segments < 1 || st.num_segments > m || st.total_lines < 0 || st.total_dir < 0)
+        return fail(TNS_EHIP, "inconsistent plan from the ingestion kernels");
+    const int64_t lines_after = plan->d_edges.used + st.total_lines;
+    const int64_t dir_after = plan->d_dir.used + st.total_dir;
+    if (lines_after > tns::kMaxEdgeOffset / tns::kSlotsPerLine) return fail(TNS_ESIZE, "edge array would exceed 2^39 slots");
+    if (dir_after / tns::kDirAlign > (int64_t)UINT32_MAX) return fail(TNS_ESIZE, "block directory would exceed its index range");
+    if ((rc = grow_device(plan->d_edges, lines_after, stream, "growing edge data"))) return rc;
+    if ((rc = grow_device(plan->d_dir, dir_after, stream, "growing the block directory"))) return rc;
+    a.dir = plan->d_dir.ptr;
+    a.lines = reinterpret_cast<uint32_t*>(plan->d_edges.ptr);
+    a.cap_lines = plan->d_edges.cap;
+    a.cap_dir = plan->d_dir.cap;
+
+    e = tns::ingest_apply(a, st.num_segments, stream);
+    if (e != hipSuccess) return fail_hip(e, "launching the ingestion kernels");
+    tns::IngestStatus done;
+    if ((rc = read_status(plan, stream, done, "waiting for the ingestion kernels"))) return rc;
+    if (done.internal) return fail(TNS_EHIP, "ingestion kernels ran out of pool space (internal error)");
+    plan->d_edges.used = lines_after;
+    plan->d_dir.used = dir_after;
+    tot.edges += m;
+    tot.next_eid += m;
+    tot.blocks += (int64_t)st.new_blocks;
+    tot.slots += (int64_t)st.new_slots;
+    return TNS_OK;
+}
+
 int tns_delete_edges(tns_plan* plan, int32_t instance, const int32_t* src, const int32_t* eid, int64_t m,
                      int64_t* num_deleted) {
     g_err.clear();
     if (!plan) return fail(TNS_EINVAL, "null plan");
     if (m < 0 || (m > 0 && (!src || !eid))) return fail(TNS_EINVAL, "null array or negative count");
-    tns::Store& s = *plan->store;
-    if (instance < 0 || instance >= s.config().num_instances) return fail(TNS_ERANGE, "instance out of range");
+    if (instance < 0 || instance >= plan->cfg.num_instances) return fail(TNS_ERANGE, "instance out of range");
     for (int64_t i = 0; i < m; ++i) {
-        if (src[i] < 0 || src[i] >= s.config().num_nodes) return fail(TNS_ERANGE, "node id outside [0, num_nodes)");
+        if (src[i] < 0 || src[i] >= plan->cfg.num_nodes) return fail(TNS_ERANGE, "node id outside [0, num_nodes)");
         if (eid[i] < 0) return fail(TNS_EINVAL, "negative edge id");
     }
+    if (plan->dev) {
+        // device-built store: the requests are copied over and applied by a kernel (default stream)
+        DeviceGuard guard(plan->cfg.device);
+        if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the plan's device");
+        int rc;
+        if ((rc = ensure_device_store(plan, nullptr))) return rc;
+        DeviceTemp<int32_t> d_src, d_eid;
+        hipError_t e = d_src.upload(src, m, nullptr);
+        if (e == hipSuccess) e = d_eid.upload(eid, m, nullptr);
+        if (e == hipSuccess)
+            e = tns::ingest_delete_edges(plan->d_nodes.ptr, plan->d_dir.ptr, reinterpret_cast<uint32_t*>(plan->d_edges.ptr),
+                                         (int64_t)instance * plan->cfg.num_nodes, d_src.ptr, d_eid.ptr, m, plan->dev->d_status,
+                                         nullptr);
+        if (e != hipSuccess) return fail_hip(e, "deleting edges on the device");
+        tns::IngestStatus st;
+        if ((rc = read_status(plan, nullptr, st, "waiting for the deletion kernel"))) return rc;
+        plan->dev->totals[(size_t)instance].deleted += (int64_t)st.counter;
+        if (num_deleted) *num_deleted = (int64_t)st.counter;
+        return TNS_OK;
+    }
+    tns::Store& s = *plan->store;
     int64_t hit = 0;
     for (int64_t i = 0; i < m; ++i) hit += s.delete_edge(instance, src[i], eid[i]);
     if (num_deleted) *num_deleted = hit;
@@ -189,10 +393,23 @@ int tns_delete_nodes(tns_plan* plan, int32_t instance, const int32_t* nodes, int
     g_err.clear();
     if (!plan) return fail(TNS_EINVAL, "null plan");
     if (m < 0 || (m > 0 && !nodes)) return fail(TNS_EINVAL, "null array or negative count");
-    tns::Store& s = *plan->store;
-    if (instance < 0 || instance >= s.config().num_instances) return fail(TNS_ERANGE, "instance out of range");
+    if (instance < 0 || instance >= plan->cfg.num_instances) return fail(TNS_ERANGE, "instance out of range");
     for (int64_t i = 0; i < m; ++i)
-        if (nodes[i] < 0 || nodes[i] >= s.config().num_nodes) return fail(TNS_ERANGE, "node id outside [0, num_nodes)");
+        if (nodes[i] < 0 || nodes[i] >= plan->cfg.num_nodes) return fail(TNS_ERANGE, "node id outside [0, num_nodes)");
+    if (plan->dev) {
+        DeviceGuard guard(plan->cfg.device);
+        if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the plan's device");
+        int rc;
+        if ((rc = ensure_device_store(plan, nullptr))) return rc;
+        DeviceTemp<int32_t> d_ids;
+        hipError_t e = d_ids.upload(nodes, m, nullptr);
+        if (e == hipSuccess)
+            e = tns::ingest_delete_nodes(plan->d_nodes.ptr, (int64_t)instance * plan->cfg.num_nodes, d_ids.ptr, m, deleted, nullptr);
+        if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+        if (e != hipSuccess) return fail_hip(e, "marking nodes on the device");
+        return TNS_OK;
+    }
+    tns::Store& s = *plan->store;
     for (int64_t i = 0; i < m; ++i) s.set_node_deleted(instance, nodes[i], deleted != 0);
     return TNS_OK;
 }
@@ -203,6 +420,7 @@ int tns_commit(tns_plan* plan, void* hip_stream) {
     DeviceGuard guard(plan->cfg.device);
     if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the plan's device");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    if (plan->dev) return ensure_device_store(plan, stream);   // nothing to upload: the store lives on the device
     tns::Store& s = *plan->store;
     int rc;
     // at least one element each, so that the kernels always get valid base pointers
@@ -480,11 +698,36 @@ int tns_traffic_model(tns_plan* plan, int64_t Q, const int32_t* d_targets, const
 int tns_stats(const tns_plan* plan, int32_t instance, tns_stats_t* out) {
     g_err.clear();
     if (!plan || !out) return fail(TNS_EINVAL, "null plan or output");
-    const tns::Store& s = *plan->store;
-    const int32_t I = s.config().num_instances;
+    const int32_t I = plan->cfg.num_instances;
     if (instance < -1 || instance >= I) return fail(TNS_ERANGE, "instance out of range");
     const int32_t i0 = instance < 0 ? 0 : instance, i1 = instance < 0 ? I : instance + 1;
     tns_stats_t r{};
+    if (plan->dev) {
+        // device-built store: totals are kept on the host, the longest list is reduced on the device
+        const DeviceStore& ds = *plan->dev;
+        for (int32_t i = i0; i < i1; ++i) {
+            const tns::InstanceTotals& t = ds.totals[(size_t)i];
+            r.num_blocks += t.blocks;
+            r.num_edges += t.edges;
+            r.wasted_slots += t.slots - t.edges;
+        }
+        const int64_t n_nodes = (int64_t)(i1 - i0) * plan->cfg.num_nodes;
+        if (ds.d_status && n_nodes > 0) {
+            DeviceGuard guard(plan->cfg.device);
+            if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the plan's device");
+            hipError_t e = tns::ingest_max_list_len(plan->d_nodes.ptr, (int64_t)i0 * plan->cfg.num_nodes, n_nodes, ds.d_status, nullptr);
+            tns::IngestStatus st{};
+            if (e == hipSuccess) e = hipMemcpy(&st, ds.d_status, sizeof(st), hipMemcpyDeviceToHost);
+            if (e != hipSuccess) return fail_hip(e, "reducing the list lengths");
+            r.max_list_len = (int64_t)st.counter;
+        }
+        r.edge_data_bytes = plan->d_edges.used * (int64_t)sizeof(tns::EdgeLine);
+        r.avg_list_len = n_nodes ? (double)r.num_blocks / (double)n_nodes : 0.0;
+        r.metadata_bytes = n_nodes * (int64_t)sizeof(tns::NodeLine) + plan->d_dir.used * (int64_t)sizeof(tns::BlockRec);
+        *out = r;
+        return TNS_OK;
+    }
+    const tns::Store& s = *plan->store;
     for (int32_t i = i0; i < i1; ++i) {
         const tns::InstanceTotals& t = s.totals(i);
         r.num_blocks += t.blocks;
@@ -510,9 +753,38 @@ int64_t tns_node_blocks(const tns_plan* plan, int32_t instance, int32_t node, in
                         int32_t* size, float* t_min, float* t_max) {
     g_err.clear();
     if (!plan) return fail(TNS_EINVAL, "null plan");
-    const tns::Store& s = *plan->store;
-    if (instance < 0 || instance >= s.config().num_instances || node < 0 || node >= s.config().num_nodes)
+    if (instance < 0 || instance >= plan->cfg.num_instances || node < 0 || node >= plan->cfg.num_nodes)
         return fail(TNS_ERANGE, "instance or node out of range");
+    if (plan->dev) {
+        // device-built store: copy the node's entry, its builder state and, for a long list, its directory run
+        if (!plan->dev->d_status) return 0;     // nothing stored yet
+        DeviceGuard guard(plan->cfg.device);
+        if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the plan's device");
+        const int64_t nidx = (int64_t)instance * plan->cfg.num_nodes + node;
+        tns::NodeLine nd;
+        tns::NodeAux ax;
+        hipError_t e = hipMemcpy(&nd, plan->d_nodes.ptr + nidx, sizeof(nd), hipMemcpyDeviceToHost);
+        if (e == hipSuccess) e = hipMemcpy(&ax, plan->dev->aux.ptr + nidx, sizeof(ax), hipMemcpyDeviceToHost);
+        if (e != hipSuccess) return fail_hip(e, "reading a node entry");
+        const int64_t n = nd.nblocks;
+        std::vector<tns::BlockRec> recs((size_t)n);
+        if (n > tns::kInlineBlocks) {
+            e = hipMemcpy(recs.data(), plan->d_dir.ptr + (int64_t)nd.dir_line * tns::kDirAlign, (size_t)n * sizeof(tns::BlockRec),
+                          hipMemcpyDeviceToHost);
+            if (e != hipSuccess) return fail_hip(e, "reading a directory run");
+        } else {
+            for (int64_t i = 0; i < n; ++i) recs[(size_t)i] = nd.rec[n - 1 - i];
+        }
+        for (int64_t i = 0; i < n && i < max_blocks; ++i) {
+            const tns::BlockRec& r = recs[(size_t)i];
+            if (cap) cap[i] = i == n - 1 ? ax.tail_cap : tns::rec_size(r);
+            if (size) size[i] = tns::rec_size(r);
+            if (t_min) t_min[i] = r.t_min;
+            if (t_max) t_max[i] = r.t_max;
+        }
+        return n;
+    }
+    const tns::Store& s = *plan->store;
     const int64_t nidx = s.node_index(instance, node);
     const int64_t n = s.nodes[nidx].nblocks;
     for (int64_t i = 0; i < n && i < max_blocks; ++i) {
@@ -533,6 +805,11 @@ int tns_destroy(tns_plan* plan) {
         plan->d_nodes.release();
         plan->d_dir.release();
         plan->d_edges.release();
+        if (plan->dev) {
+            plan->dev->aux.release();
+            plan->dev->ws.release();
+            if (plan->dev->d_status) (void)hipFree(plan->dev->d_status);
+        }
     }
     delete plan;
     return TNS_OK;

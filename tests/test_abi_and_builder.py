@@ -41,7 +41,9 @@ def test_argument_validation():
                        (dict(num_nodes=4, fanout=3, num_instances=0), B.TNS_EINVAL),
                        (dict(num_nodes=4, fanout=3, sizing=3), B.TNS_EINVAL),
                        (dict(num_nodes=4, fanout=3, inclusive_end=2), B.TNS_EINVAL),
-                       (dict(num_nodes=4, fanout=3, flags=16), B.TNS_EINVAL),
+                       (dict(num_nodes=4, fanout=3, flags=32), B.TNS_EINVAL),
+                       (dict(num_nodes=4, fanout=3, flags=B.TNS_FLAG_DEVICE_INGEST | B.TNS_FLAG_EDGES_ON_HOST), B.TNS_EINVAL),
+                       (dict(num_nodes=4, fanout=3, flags=B.TNS_FLAG_DEVICE_INGEST | B.TNS_FLAG_NO_NODE_SLAB), B.TNS_EINVAL),
                        (dict(num_nodes=4, fanout=3, flags=B.TNS_FLAG_EDGES_ON_HOST | B.TNS_FLAG_ALL_ON_HOST), B.TNS_EINVAL)]:
         with pytest.raises(B.TnsError) as ei:
             B.tns_plan_create(**kw)
@@ -50,6 +52,15 @@ def test_argument_validation():
     with pytest.raises(B.TnsError) as ei:
         B.tns_add_edges(h, 0, [4], [0], [1.0])
     assert ei.value.status == B.TNS_ERANGE
+    # a store built on the device takes no host batches, and a host-built one no device batches
+    hd = B.tns_plan_create(num_nodes=4, fanout=3, flags=B.TNS_FLAG_DEVICE_INGEST)
+    with pytest.raises(B.TnsError) as ei:
+        B.tns_add_edges(hd, 0, [1], [0], [1.0])
+    assert ei.value.status == B.TNS_ESTATE
+    B.tns_destroy(hd)
+    with pytest.raises(B.TnsError) as ei:
+        B.tns_add_edges_device(h, 0, 0, 0, 0, None, 0, None)
+    assert ei.value.status == B.TNS_ESTATE
     with pytest.raises(B.TnsError) as ei:
         B.tns_add_edges(h, 0, [-1], [0], [1.0])
     assert ei.value.status == B.TNS_ERANGE

@@ -88,6 +88,9 @@ def main() -> int:
     ap.add_argument("--placement", default="hbm", choices=["hbm", "hybrid", "host"],
                     help="hbm: the whole store in device memory (default); hybrid: edge data in page-locked host "
                          "memory, metadata on the device (the paper's placement); host: everything in host memory")
+    ap.add_argument("--ingest", default="host", choices=["host", "device"],
+                    help="host: tns_add_edges + tns_commit (default); device: the stream is copied to the GPU once and "
+                         "ingested batch by batch with tns_add_edges_device")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (torch copy_) so that rocprofv3 counter runs of this "
                          "command contain a kernel of known traffic")
@@ -122,14 +125,24 @@ def main() -> int:
     plan = B.Plan(wl.num_nodes, f, policy=policy, block_threshold=wl.tau, num_instances=wl.num_instances,
                   seed=wl.seed,
                   flags=(B.TNS_FLAG_NO_XCD_REMAP if args.no_remap else 0)
-                  | {"hbm": 0, "hybrid": B.TNS_FLAG_EDGES_ON_HOST, "host": B.TNS_FLAG_ALL_ON_HOST}[args.placement])
+                  | {"hbm": 0, "hybrid": B.TNS_FLAG_EDGES_ON_HOST, "host": B.TNS_FLAG_ALL_ON_HOST}[args.placement]
+                  | (B.TNS_FLAG_DEVICE_INGEST if args.ingest == "device" else 0))
     last = time.time()
     for i, st in enumerate(wl.streams):
+        if args.ingest == "device":
+            d_src, d_dst, d_ts = (torch.from_numpy(a).to(dev) for a in (st.src, st.dst, st.ts))
+            torch.cuda.synchronize()
+            t0 = time.time() if i == 0 else t0      # the one-off copy of the stream is not ingestion
         for lo, hi in st.batches():
-            B.tns_add_edges(plan.handle, i, st.src[lo:hi], st.dst[lo:hi], st.ts[lo:hi], None)
+            if args.ingest == "device":
+                plan.add_edges_device(d_src[lo:hi], d_dst[lo:hi], d_ts[lo:hi], instance=i)
+            else:
+                B.tns_add_edges(plan.handle, i, st.src[lo:hi], st.dst[lo:hi], st.ts[lo:hi], None)
             if time.time() - last > 20:
                 log(f"  instance {i}: {hi}/{st.n} edges")
                 last = time.time()
+        if args.ingest == "device":
+            del d_src, d_dst, d_ts
     ingest_s = time.time() - t0
     t0 = time.time()
     plan.commit()
@@ -228,7 +241,7 @@ def main() -> int:
         "config": {"workload": f"{wl.name}: {wl.description}; query i = (src[i], -inf, ts[i]); f={f}, tau={wl.tau}, "
                                f"policy={args.policy}, window={'0.25 span' if args.windowed else 'unbounded'}",
                    "queries": Q, "instances": wl.num_instances, "nodes_per_instance": wl.num_nodes,
-                   "placement": args.placement},
+                   "placement": args.placement, "ingest": args.ingest},
         "roofline": {"bound": "hbm", "kernel": "tns_sample_kernel (padding removal fused)" if args.policy == "recent" else "tns_sample_kernel + tns_compact kernels (whole step)", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic(wl.name, args.policy) if args.placement == "hbm" else None,

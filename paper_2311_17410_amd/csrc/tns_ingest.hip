@@ -360,11 +360,22 @@ __global__ void __launch_bounds__(kThreads) k_plan(const IngestArgs a, const uin
         need_lines[s] = lines;
         need_dir[s] = dirs;
     }
+    // totals: one pair of atomics per workgroup (atomics on one word serialise)
+    __shared__ int64_t s_blocks[kThreads / kWave], s_slots[kThreads / kWave];
     blocks = wave_sum64(blocks);
     slots = wave_sum64(slots);
-    if ((threadIdx.x & (kWave - 1)) == 0 && blocks) {
-        atomicAdd(&a.status->new_blocks, (unsigned long long)blocks);
-        atomicAdd(&a.status->new_slots, (unsigned long long)slots);
+    if ((threadIdx.x & (kWave - 1)) == 0) {
+        s_blocks[threadIdx.x / kWave] = blocks;
+        s_slots[threadIdx.x / kWave] = slots;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        blocks = s_blocks[0] + s_blocks[1] + s_blocks[2] + s_blocks[3];
+        slots = s_slots[0] + s_slots[1] + s_slots[2] + s_slots[3];
+        if (blocks) {
+            atomicAdd(&a.status->new_blocks, (unsigned long long)blocks);
+            atomicAdd(&a.status->new_slots, (unsigned long long)slots);
+        }
     }
 }
 

@@ -120,3 +120,28 @@ def test_c5_windowed_sampled_chunks(c5):
     for c in (3, 12):
         _compare_chunk(c5, c, 0, t_start, 0, None)
         progress(f"C5 windowed: chunk {c} matches")
+
+
+def test_c5_store_built_on_the_device(c5):
+    """The same stream ingested on the GPU (tns_add_edges_device, 2^17-edge batches): same block
+    statistics as the host builder, and the full-size run matches the oracle on sampled chunks."""
+    B, st, torch, wl = c5["B"], c5["st"], c5["torch"], c5["wl"]
+    dplan = B.Plan(st.num_nodes, wl.fanout, block_threshold=wl.tau, flags=B.TNS_FLAG_DEVICE_INGEST)
+    d_dst = torch.from_numpy(st.dst).to(c5["d"]["t_end"].device)
+    progress("C5 device-built: ingesting 2^28 edges on the GPU")
+    for i, (lo, hi) in enumerate(st.batches()):
+        dplan.add_edges_device(c5["d"]["targets"][lo:hi], d_dst[lo:hi], c5["d"]["t_end"][lo:hi])
+        if i % 512 == 511:
+            progress(f"C5 device-built: {hi} edges ingested")
+    del d_dst
+    hs, ds = c5["plan"].stats(), dplan.stats()
+    for k in ("num_blocks", "num_edges", "wasted_slots", "max_list_len"):
+        assert hs[k] == ds[k], k
+    progress("C5 device-built: GPU run over 2^28 queries")
+    dplan.run(c5["d"]["targets"], None, c5["d"]["t_end"], out=c5["out"])
+    torch.cuda.synchronize()
+    assert int(c5["out"]["workspace"][4:8].view(torch.int32).item()) == 0
+    for c in (2, 14):
+        _compare_chunk(c5, c, 0, None, 0, None)
+        progress(f"C5 device-built: chunk {c} matches")
+    dplan.close()

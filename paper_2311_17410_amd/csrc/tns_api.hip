@@ -74,6 +74,7 @@ struct tns_plan {
     std::unique_ptr<DeviceStore> dev;           // device builder (null otherwise)
     DeviceArray<tns::NodeLine> d_nodes;
     DeviceArray<tns::BlockRec> d_dir;
+    DeviceArray<uint32_t> d_dir_cum;            // per directory record: the node's edges in older blocks
     DeviceArray<tns::EdgeLine> d_edges;
     bool committed = false;
 };
@@ -152,6 +153,7 @@ int ensure_device_store(tns_plan* plan, hipStream_t stream) {
     if ((rc = grow_device(plan->d_nodes, total_nodes, stream, "allocating node table"))) return rc;
     if ((rc = grow_device(ds.aux, total_nodes, stream, "allocating the builder state"))) return rc;
     if ((rc = grow_device(plan->d_dir, 1024, stream, "allocating the block directory"))) return rc;
+    if ((rc = grow_device(plan->d_dir_cum, 1024, stream, "allocating the block directory"))) return rc;
     if ((rc = grow_device(plan->d_edges, 1024, stream, "allocating edge data"))) return rc;
     hipError_t e = hipMemsetAsync(plan->d_nodes.ptr, 0, (size_t)total_nodes * sizeof(tns::NodeLine), stream);
     if (e == hipSuccess) e = hipMemsetAsync(ds.aux.ptr, 0, (size_t)total_nodes * sizeof(tns::NodeAux), stream);
@@ -215,7 +217,7 @@ int tns_plan_create(const tns_config* cfg, tns_plan** out) {
         std::unique_ptr<tns_plan> p(new tns_plan());
         p->cfg = *cfg;
         p->d_edges.on_host = (cfg->flags & (TNS_FLAG_EDGES_ON_HOST | TNS_FLAG_ALL_ON_HOST)) != 0;
-        p->d_nodes.on_host = p->d_dir.on_host = (cfg->flags & TNS_FLAG_ALL_ON_HOST) != 0;
+        p->d_nodes.on_host = p->d_dir.on_host = p->d_dir_cum.on_host = (cfg->flags & TNS_FLAG_ALL_ON_HOST) != 0;
         if (cfg->flags & TNS_FLAG_DEVICE_INGEST) {
             p->dev.reset(new DeviceStore());
             p->dev->totals.resize((size_t)cfg->num_instances);
@@ -297,6 +299,7 @@ int tns_add_edges_device(tns_plan* plan, int32_t instance, const int32_t* d_src,
     a.nodes = plan->d_nodes.ptr;
     a.aux = ds.aux.ptr;
     a.dir = plan->d_dir.ptr;
+    a.dir_cum = plan->d_dir_cum.ptr;
     a.lines = reinterpret_cast<uint32_t*>(plan->d_edges.ptr);
     a.node_base = (int64_t)instance * plan->cfg.num_nodes;
     a.num_nodes = plan->cfg.num_nodes;
@@ -333,10 +336,12 @@ int tns_add_edges_device(tns_plan* plan, int32_t instance, const int32_t* d_src,
     if (dir_after / tns::kDirAlign > (int64_t)UINT32_MAX) return fail(TNS_ESIZE, "block directory would exceed its index range");
     if ((rc = grow_device(plan->d_edges, lines_after, stream, "growing edge data"))) return rc;
     if ((rc = grow_device(plan->d_dir, dir_after, stream, "growing the block directory"))) return rc;
+    if ((rc = grow_device(plan->d_dir_cum, dir_after, stream, "growing the block directory"))) return rc;
     a.dir = plan->d_dir.ptr;
+    a.dir_cum = plan->d_dir_cum.ptr;
     a.lines = reinterpret_cast<uint32_t*>(plan->d_edges.ptr);
     a.cap_lines = plan->d_edges.cap;
-    a.cap_dir = plan->d_dir.cap;
+    a.cap_dir = std::min(plan->d_dir.cap, plan->d_dir_cum.cap);
 
     e = tns::ingest_apply(a, st.num_segments, stream);
     if (e != hipSuccess) return fail_hip(e, "launching the ingestion kernels");
@@ -345,6 +350,7 @@ int tns_add_edges_device(tns_plan* plan, int32_t instance, const int32_t* d_src,
     if (done.internal) return fail(TNS_EHIP, "ingestion kernels ran out of pool space (internal error)");
     plan->d_edges.used = lines_after;
     plan->d_dir.used = dir_after;
+    plan->d_dir_cum.used = dir_after;
     tot.edges += m;
     tot.next_eid += m;
     tot.blocks += (int64_t)st.new_blocks;
@@ -426,14 +432,17 @@ int tns_commit(tns_plan* plan, void* hip_stream) {
     // at least one element each, so that the kernels always get valid base pointers
     if ((rc = ensure_capacity(plan->d_nodes, std::max<int64_t>(s.nodes.size(), 1), s.nodes, "allocating node table"))) return rc;
     if ((rc = ensure_capacity(plan->d_dir, std::max<int64_t>(s.dir.size(), 1), s.dir, "allocating the block directory"))) return rc;
+    if ((rc = ensure_capacity(plan->d_dir_cum, std::max<int64_t>(s.dir_cum.size(), 1), s.dir_cum, "allocating the block directory"))) return rc;
     if ((rc = ensure_capacity(plan->d_edges, std::max<int64_t>(s.lines.size(), 1), s.lines, "allocating edge data"))) return rc;
     if ((rc = upload_dirty(plan->d_nodes, s.nodes, stream, "uploading node table"))) return rc;
     if ((rc = upload_dirty(plan->d_dir, s.dir, stream, "uploading the block directory"))) return rc;
+    if ((rc = upload_dirty(plan->d_dir_cum, s.dir_cum, stream, "uploading the block directory"))) return rc;
     if ((rc = upload_dirty(plan->d_edges, s.lines, stream, "uploading edge data"))) return rc;
     const hipError_t e = hipStreamSynchronize(stream);
     if (e != hipSuccess) return fail_hip(e, "waiting for the upload");
     s.nodes.clear_dirty();
     s.dir.clear_dirty();
+    s.dir_cum.clear_dirty();
     s.lines.clear_dirty();
     plan->committed = true;
     return TNS_OK;
@@ -469,6 +478,7 @@ static int fill_sample_args(tns_plan* plan, int64_t Q, const int32_t* d_targets,
     a.delta = INFINITY;
     a.nodes = plan->d_nodes.ptr;
     a.dir = plan->d_dir.ptr;
+    a.dir_cum = plan->d_dir_cum.ptr;
     a.edges = reinterpret_cast<const uint32_t*>(plan->d_edges.ptr);
     a.targets = d_targets;
     a.t_start = d_t_start;
@@ -804,6 +814,7 @@ int tns_destroy(tns_plan* plan) {
         DeviceGuard guard(plan->cfg.device);
         plan->d_nodes.release();
         plan->d_dir.release();
+        plan->d_dir_cum.release();
         plan->d_edges.release();
         if (plan->dev) {
             plan->dev->aux.release();

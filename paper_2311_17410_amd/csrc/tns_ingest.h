@@ -48,6 +48,7 @@ struct IngestArgs {
     NodeLine* nodes;
     NodeAux* aux;
     BlockRec* dir;
+    uint32_t* dir_cum;    // per directory record: the node's edges in older blocks
     uint32_t* lines;      // edge lines as 4-byte words
     int64_t node_base;    // instance * num_nodes
     int64_t num_nodes;

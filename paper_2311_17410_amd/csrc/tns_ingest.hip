@@ -398,6 +398,7 @@ __global__ void __launch_bounds__(kThreads) k_apply_nodes(const IngestArgs a, co
         const BlockRec o = *tr;
         *tr = make_rec(o.t_min, a.ts[val[p0 + P.take - 1]], rec_off(o), rec_size(o) + P.take, rec_tombstones(o));
     }
+    const int64_t degree_before = N->degree;
     N->degree += (int32_t)mm;
     if (P.nbn > 0) {
         const int64_t lines = lines_of_blocks(P.cap, P.nbn, P.k0);
@@ -412,11 +413,22 @@ __global__ void __launch_bounds__(kThreads) k_apply_nodes(const IngestArgs a, co
                 const int64_t start = a.used_dir + dir_base[s];
                 if (start + n > a.cap_dir) { atomicOr(&a.status->internal, 2u); return; }
                 BlockRec* dst = a.dir + start;
+                uint32_t* dcum = a.dir_cum + start;
                 if (nb <= kInlineBlocks) {
-                    for (int j = 0; j < nb; ++j) dst[j] = N->rec[nb - 1 - j];           // oldest first
+                    uint32_t before = 0;
+                    for (int j = 0; j < nb; ++j) {                                       // oldest first
+                        const BlockRec o = N->rec[nb - 1 - j];
+                        dst[j] = o;
+                        dcum[j] = before;
+                        before += (uint32_t)rec_size(o);
+                    }
                 } else {
                     const BlockRec* old = a.dir + (int64_t)N->dir_line * kDirAlign;
-                    for (int32_t j = 0; j < nb; ++j) dst[j] = old[j];
+                    const uint32_t* ocum = a.dir_cum + (int64_t)N->dir_line * kDirAlign;
+                    for (int32_t j = 0; j < nb; ++j) {
+                        dst[j] = old[j];
+                        dcum[j] = ocum[j];
+                    }
                 }
                 N->dir_line = (uint32_t)(start / kDirAlign);
                 ax.dir_cap = (int32_t)n;
@@ -425,12 +437,17 @@ __global__ void __launch_bounds__(kThreads) k_apply_nodes(const IngestArgs a, co
         } else {
             for (int j = nb - 1; j >= 0; --j) N->rec[j + P.nbn] = N->rec[j];            // newest first: make room in front
         }
+        uint32_t* run_cum = run ? a.dir_cum + (int64_t)N->dir_line * kDirAlign : nullptr;
         for (int32_t j = 0; j < P.nbn; ++j) {
             const int64_t first = (int64_t)p0 + P.take + (int64_t)j * P.cap;
             const int64_t size = min((int64_t)P.cap, rest - (int64_t)j * P.cap);
             const BlockRec r = make_rec(a.ts[val[first]], a.ts[val[first + size - 1]], block_slot(P, line0, j), (int32_t)size);
-            if (run) run[nb + j] = r;
-            else N->rec[P.nbn - 1 - j] = r;
+            if (run) {
+                run[nb + j] = r;
+                run_cum[nb + j] = (uint32_t)(degree_before + P.take + (int64_t)j * P.cap);   // edges in the older blocks
+            } else {
+                N->rec[P.nbn - 1 - j] = r;
+            }
         }
         N->nblocks = (int32_t)after;
         ax.tail_cap = P.cap;

@@ -13,6 +13,7 @@ struct SampleArgs {
     // store (device)
     const NodeLine* nodes;
     const BlockRec* dir;     // directory pool: record runs of nodes with more than kInlineBlocks blocks
+    const uint32_t* dir_cum; // same indexing: number of the node's edges stored in the blocks before this one
     const uint32_t* edges;   // edge lines viewed as 4-byte words: slot s starts at word slot_word(s)
     // queries (device)
     const int32_t* targets;

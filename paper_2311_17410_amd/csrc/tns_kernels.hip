@@ -14,7 +14,7 @@
 
 #include <algorithm>
 #include <cstdlib>
-#include <cstdlib>
+#include <type_traits>
 
 namespace tns {
 namespace {
@@ -436,7 +436,51 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
             } else if (nb > kInlineBlocks) {
                 // long list: all records of the node, oldest first, in one run of the directory
                 const int64_t d0 = (int64_t)h.z * kDirAlign;
-                if (d0 + nb <= p.num_dir) {
+                if (POLICY == 1 && d0 + nb <= p.num_dir && !(h.w & 2)) {
+                    // Uniform policy on a long list without deleted edges: the node's edges, blocks
+                    // concatenated, form one chronological sequence and the candidates are a contiguous
+                    // range [L, R) of it.  With the number of edges before each block kept next to the
+                    // records, both ends and every pick cost a binary search over the run instead of
+                    // two walks over all overlapping blocks.
+                    const BlockRec* __restrict__ d = p.dir + d0;
+                    const uint32_t* __restrict__ cum = p.dir_cum + d0;
+                    // index in the sequence of the first edge with ts >= x (STRICT: ts > x)
+                    auto first_at = [&](float x, auto strict) -> int64_t {
+                        constexpr bool STRICT = decltype(strict)::value;
+                        int32_t lo = 0, hi = nb;          // first block whose newest edge is not before x
+                        while (lo < hi) {
+                            const int32_t mid = lo + ((hi - lo) >> 1);
+                            const float tm = d[mid].t_max;
+                            ++w.n_blocks;
+                            if (STRICT ? (tm > x) : (tm >= x)) hi = mid; else lo = mid + 1;
+                        }
+                        if (lo == nb) return (int64_t)cum[nb - 1] + rec_size(d[nb - 1]);
+                        const BlockRec r = d[lo];
+                        ++w.n_blocks;
+                        int32_t pos = 0;
+                        if (!(STRICT ? (r.t_min > x) : (r.t_min >= x)))
+                            pos = w.template first_not_before<STRICT>(rec_off(r), rec_size(r), x);
+                        return (int64_t)cum[lo] + pos;
+                    };
+                    const int64_t R = first_at(w.te, std::integral_constant<bool, INCL>{});
+                    const int64_t L = w.tb == -INFINITY ? 0 : first_at(w.tb, std::false_type{});
+                    const int64_t c = R > L ? R - L : 0;
+                    const int32_t kk = (int32_t)min(c, (int64_t)f);
+                    for (int32_t j = 0; j < kk; ++j) {
+                        const int64_t g = c <= (int64_t)f ? R - 1 - j
+                                                          : L + (int64_t)pick_rank(p.seed, p.qid_base + q, f, j, (uint64_t)c);
+                        int32_t lo = 0, hi = nb;          // newest block that starts at or before g
+                        while (lo < hi) {
+                            const int32_t mid = lo + ((hi - lo) >> 1);
+                            ++w.n_probes;
+                            if ((int64_t)cum[mid] <= g) lo = mid + 1; else hi = mid;
+                        }
+                        const int32_t b = lo - 1;
+                        ++w.n_blocks;
+                        w.s_pos[j] = (pos_t)slot_word(rec_off(d[b]) + (g - (int64_t)cum[b]));
+                    }
+                    w.k = kk;
+                } else if (d0 + nb <= p.num_dir) {
                     const BlockRec* __restrict__ d = p.dir + d0;
                     // newest block that starts before the window end (binary search instead of
                     // stepping through the newer blocks one by one)

@@ -94,17 +94,29 @@ void Store::append_block(int64_t nidx, NodeLine& nd, const BlockRec& r, int32_t 
         if (nd.nblocks == dcap || dcap == 0) {
             const int32_t ncap = dcap ? dcap * 2 : 2 * kDirAlign;
             const int64_t start = dir.grow(ncap);
+            dir_cum.grow(ncap);
             if (dcap == 0) {
-                for (int j = 0; j < kInlineBlocks; ++j) dir.raw(start + j) = nd.rec[kInlineBlocks - 1 - j];
+                uint32_t before = 0;
+                for (int j = 0; j < kInlineBlocks; ++j) {
+                    const BlockRec& o = nd.rec[kInlineBlocks - 1 - j];
+                    dir.raw(start + j) = o;
+                    dir_cum.raw(start + j) = before;
+                    before += (uint32_t)rec_size(o);
+                }
             } else {
                 const int64_t old = (int64_t)nd.dir_line * kDirAlign;
-                for (int32_t j = 0; j < nd.nblocks; ++j) dir.raw(start + j) = dir[old + j];
+                for (int32_t j = 0; j < nd.nblocks; ++j) {
+                    dir.raw(start + j) = dir[old + j];
+                    dir_cum.raw(start + j) = dir_cum[old + j];
+                }
             }
             dir.mark(start, nd.nblocks);
+            dir_cum.mark(start, nd.nblocks);
             nd.dir_line = (uint32_t)(start / kDirAlign);
             dcap = ncap;
         }
         dir.mut((int64_t)nd.dir_line * kDirAlign + nd.nblocks) = r;
+        dir_cum.mut((int64_t)nd.dir_line * kDirAlign + nd.nblocks) = (uint32_t)nd.degree;   // edges in the older blocks
     }
     nd.nblocks += 1;
     tail_cap_[(size_t)nidx] = cap;

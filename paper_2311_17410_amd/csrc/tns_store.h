@@ -123,6 +123,7 @@ public:
 
     Paged<NodeLine, 18, 9> nodes;   // 128-byte entries: 2^18 per page, change tracking per 64 KiB
     Paged<BlockRec> dir;            // directory pool: record runs of nodes with long lists
+    Paged<uint32_t> dir_cum;        // same indexing as dir: edges the node holds in the blocks before this one
     Paged<EdgeLine, 18, 9> lines;   // edge data, 10 slots per 128-byte line
 
     Edge& edge_at(int64_t slot) { return lines.raw(slot / kSlotsPerLine).e[slot % kSlotsPerLine]; }

@@ -733,7 +733,7 @@ int tns_stats(const tns_plan* plan, int32_t instance, tns_stats_t* out) {
         }
         r.edge_data_bytes = plan->d_edges.used * (int64_t)sizeof(tns::EdgeLine);
         r.avg_list_len = n_nodes ? (double)r.num_blocks / (double)n_nodes : 0.0;
-        r.metadata_bytes = n_nodes * (int64_t)sizeof(tns::NodeLine) + plan->d_dir.used * (int64_t)sizeof(tns::BlockRec);
+        r.metadata_bytes = n_nodes * (int64_t)sizeof(tns::NodeLine) + plan->d_dir.used * (int64_t)(sizeof(tns::BlockRec) + sizeof(uint32_t));
         *out = r;
         return TNS_OK;
     }
@@ -754,7 +754,7 @@ int tns_stats(const tns_plan* plan, int32_t instance, tns_stats_t* out) {
     const int64_t n_nodes = (int64_t)(i1 - i0) * s.config().num_nodes;
     r.avg_list_len = n_nodes ? (double)r.num_blocks / (double)n_nodes : 0.0;
     // node lines of the instance(s) plus the directory pool (shared by all instances, counted in full)
-    r.metadata_bytes = n_nodes * (int64_t)sizeof(tns::NodeLine) + s.dir.size() * (int64_t)sizeof(tns::BlockRec);
+    r.metadata_bytes = n_nodes * (int64_t)sizeof(tns::NodeLine) + s.dir.size() * (int64_t)(sizeof(tns::BlockRec) + sizeof(uint32_t));
     *out = r;
     return TNS_OK;
 }

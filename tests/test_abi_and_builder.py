@@ -101,7 +101,8 @@ def test_sizing_closed_forms():
     caps = list(B.tns_node_blocks(h, 0, 0)["cap"])
     assert caps[:6] == [1, 1, 2, 4, 8, 16] and set(caps[6:]) == {16}
     # 11 blocks > 7 inline records: the node's records moved to a 16-record directory run
-    assert len(caps) == 11 and B.tns_stats(h)["metadata_bytes"] == 128 + 16 * 16
+    # (16-byte record + 4-byte cumulative edge count each)
+    assert len(caps) == 11 and B.tns_stats(h)["metadata_bytes"] == 128 + 16 * (16 + 4)
     blk = B.tns_node_blocks(h, 0, 0)
     assert list(blk["t_min"][:4]) == [0.0, 1.0, 2.0, 4.0] and blk["t_max"][-1] == 99.0
     B.tns_destroy(h)

@@ -1,0 +1,127 @@
+#!/usr/bin/env python3
+"""Bench of multi-hop sampling (section 4.2 of the paper: the nodes sampled in one layer are the
+targets of the next; a "next" row of the scope).
+
+A step is one tns_run_khop call: every hop is a full pass of the hot path (sampling with the padding
+removal fused in) whose queries are the dense output of the hop before, chained on the device.
+Workload: the C5 recipe (uniform node ids, |V| = n/16, sorted U[0,1) times) with one first-hop query
+per event.  Prints one JSON line.
+
+    python bench_khop.py [--log2n 24] [--fanouts 10,10] [--steps K] [--warmup W]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--log2n", type=int, default=24)
+    ap.add_argument("--fanouts", default="10,10")
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench_khop.py: one GPU only", file=sys.stderr)
+        return 2
+    import numpy as np
+    import torch
+    from paper_2311_17410_amd import binding as B
+    from paper_2311_17410_amd import workloads as W
+
+    B.lib()
+    dev = torch.device("cuda", 0)
+    fanouts = [int(x) for x in args.fanouts.split(",")]
+    wl = W.c5(log2_n=args.log2n)
+    st = wl.streams[0]
+    Q = st.n
+    plan = B.Plan(st.num_nodes, fanouts[0], block_threshold=wl.tau, flags=B.TNS_FLAG_DEVICE_INGEST)
+    d_src, d_dst, d_ts = (torch.from_numpy(a).to(dev) for a in (st.src, st.dst, st.ts))
+    for lo, hi in st.batches():
+        plan.add_edges_device(d_src[lo:hi], d_dst[lo:hi], d_ts[lo:hi])
+    del d_dst
+
+    hops, ws = plan.run_khop(fanouts, d_src, None, d_ts)           # allocates the per-hop buffers once
+    torch.cuda.synchronize()
+    p = lambda t: 0 if t is None else t.data_ptr()
+    ptrs = [{k: p(v) for k, v in h.items() if k not in ("cap", "fanout")} for h in hops]
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step():
+        B.tns_run_khop(plan.handle, fanouts, float("inf"), Q, p(d_src), 0, p(d_ts), 0, 0, ptrs, ws.data_ptr(), ws.numel(), stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_gpu = ev0.elapsed_time(ev1) / args.steps
+
+    # queries per hop and the byte model (the library's counting pass on each hop's queries)
+    n_q = [Q]
+    for h in hops[:-1]:
+        n_q.append(int(h["rowptr"][n_q[-1]].item()))
+    alg, targets, t_end = 0, d_src, d_ts
+    counters = torch.zeros(4, dtype=torch.int64, device=dev)
+    for h, f, q in zip(hops, fanouts, n_q):
+        plan.set_sampler(f, B.TNS_POLICY_RECENT, 0, 0)
+        counters.zero_()
+        B.tns_traffic_model(plan.handle, q, p(targets), 0, p(t_end), 0, 0, counters.data_ptr(), stream)
+        torch.cuda.synchronize()
+        nn, nb, npr, ne = (int(x) for x in counters.cpu())
+        alg += 8 * q + 16 * nn + 16 * nb + 4 * npr + 12 * ne + (12 * f + 4) * q + 8 * (q + 1) + 12 * ne
+        targets, t_end = h["cmp_nbr"], h["cmp_ts"]
+    total_q = sum(n_q)
+
+    cpu = None
+    if args.cpu_seconds > 0:
+        import oracle
+        adj = oracle.Adjacency(st.num_nodes, st.src, st.dst, st.ts)
+        k = min(Q, 1 << 22)
+        t0 = time.perf_counter()
+        tg, te, done, ok = st.src[:k], st.ts[:k], 0, True
+        for h, f in zip(hops, fanouts):
+            ref = adj.sample(tg, None, te, f, policy=0, threads=16)
+            rowptr, cn, ce, ct = oracle.compact(ref)
+            done += len(tg)
+            ok = ok and bool(np.array_equal(h["cmp_eid"][:len(ce)].cpu().numpy(), ce))
+            tg, te = cn, ct
+        cpu_s = time.perf_counter() - t0
+        cpu = {"value": done / cpu_s, "unit": "elements/s", "cores": 16, "kind": "oracle",
+               "sample": f"the first {k} first-hop queries and everything they expand to ({done} queries), {cpu_s:.1f} s "
+                         "including the comparison with the GPU output", "matches_gpu_on_sample": ok}
+        adj.close()
+
+    print(json.dumps({
+        "metric": "hot-path elements/sec over all hops at 1 MI355X", "value": total_q / (ms * 1e-3), "unit": "elements/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+        "dtype": "int32 ids / fp32 timestamps (copied and compared, no arithmetic)", "data": "synthetic",
+        "config": {"workload": f"{wl.name} recipe, n=2^{args.log2n}: one first-hop query per event, fan-outs {fanouts}, recent "
+                               "policy, unbounded window, hop h+1 = dense output of hop h", "queries_per_hop": n_q},
+        "roofline": {"bound": "hbm", "achieved": alg / (ms_gpu * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
+                     "frac": alg / (ms_gpu * 1e-3) / 1e9 / 8000.0, "traffic": None, "algorithmic_bytes_per_step": alg,
+                     "ms_gpu_per_step": ms_gpu},
+        "cpu_baseline": cpu,
+    }), flush=True)
+    plan.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -68,11 +68,17 @@ def cpu_baseline(wl, policy: int, seed: int, target_seconds: float, d_out, torch
             ok = bool(np.array_equal(g_eid, ref.eid) and np.array_equal(g_cnt, ref.count))
         done += len(sel)
         pos += chunk * stride
+    # one thread, on a prefix sized for a few seconds
+    n1 = min(st.n, 1 << 22)
+    t0 = time.time()
+    adj.sample(st.src[:n1], None, st.ts[:n1], f, policy=policy, seed=seed, q_ids=np.arange(n1, dtype=np.int64), threads=1)
+    one_s = time.time() - t0
     adj.close()
     return {"value": done / spent, "unit": "elements/s", "cores": used, "kind": "oracle",
             "sample": f"every {stride}th query of the batch from query 0 on, {done} queries, {spent:.1f} s "
                       f"(per-node list build {build_s:.1f} s not included)",
-            "matches_gpu_on_sample": ok}
+            "matches_gpu_on_sample": ok,
+            "single_thread": {"value": n1 / one_s, "unit": "elements/s", "sample": f"the first {n1} queries, {one_s:.1f} s"}}
 
 
 def main() -> int:
@@ -92,8 +98,8 @@ def main() -> int:
                     help="host: tns_add_edges + tns_commit (default); device: the stream is copied to the GPU once and "
                          "ingested batch by batch with tns_add_edges_device")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run a plain 1 GiB device copy (torch copy_) so that rocprofv3 counter runs of this "
-                         "command contain a kernel of known traffic")
+                    help="accepted for the recorded profile commands: the plain 1 GiB device copy of known traffic "
+                         "now always runs (it also gives the box's streaming ceiling)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU oracle time budget (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -218,17 +224,30 @@ def main() -> int:
     torch.cuda.synchronize()
     ms_sample = sum(e[0].elapsed_time(e[1]) for e in ev2) / args.steps
     ms_compact = sum(e[1].elapsed_time(e[2]) for e in ev2) / args.steps
-    if args.calibrate_copy:
-        a = torch.arange(1 << 28, dtype=torch.int32, device=dev)
-        b = torch.empty_like(a)
-        for _ in range(3):
-            b.copy_(a)
-        torch.cuda.synchronize()
-        del a, b
+    # the box's own streaming ceiling: a plain 1 GiB device copy (reads 1 GiB, writes 1 GiB); the same
+    # kernel gives rocprofv3 counter runs of this command a launch of known traffic (--calibrate-copy)
+    a = torch.arange(1 << 28, dtype=torch.int32, device=dev)
+    b = torch.empty_like(a)
+    b.copy_(a)
+    evc = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    evc[0].record()
+    for _ in range(5):
+        b.copy_(a)
+    evc[1].record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * a.numel() * 4 / (evc[0].elapsed_time(evc[1]) * 1e-3) / 1e9
+    del a, b
     total_k = int(out["rowptr"][-1].item())
     assert total_k == n_edges, (total_k, n_edges)
 
     achieved = alg_step / (ms_kernel * 1e-3) / 1e9
+    per_step = sorted(e[0].elapsed_time(e[1]) for e in ev)
+    traffic = measured_traffic(wl.name, args.policy) if args.placement == "hbm" else None
+    moved = None
+    if traffic:
+        moved_gbs = traffic / (ms_kernel * 1e-3) / 1e9
+        moved = {"GBs": moved_gbs, "frac_of_peak": moved_gbs / HBM_PEAK_GBS, "frac_of_copy_ceiling": moved_gbs / copy_gbs,
+                 "waste_factor": traffic / alg_step}
     bytes_step = dict(bytes_sample, dense_write=dense_write)
     result = {
         "metric": "hot-path elements/sec at 1 MI355X + % of HBM/MFMA roofline",
@@ -244,9 +263,10 @@ def main() -> int:
                    "placement": args.placement, "ingest": args.ingest},
         "roofline": {"bound": "hbm", "kernel": "tns_sample_kernel (padding removal fused)" if args.policy == "recent" else "tns_sample_kernel + tns_compact kernels (whole step)", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": measured_traffic(wl.name, args.policy) if args.placement == "hbm" else None,
+                     "traffic": traffic, "moved": moved, "copy_ceiling_GBs": copy_gbs,
                      "algorithmic_bytes_per_launch": alg_step, "bytes_breakdown": bytes_step,
-                     "ms_per_launch": ms_kernel},
+                     "ms_per_launch": ms_kernel, "ms_per_launch_median": per_step[len(per_step) // 2],
+                     "ms_per_launch_min": per_step[0]},
         "two_kernel_path": {"sample_ms": ms_sample, "sample_GBs": alg_sample / (ms_sample * 1e-3) / 1e9,
                             "compact_ms": ms_compact, "compact_GBs": alg_compact / (ms_compact * 1e-3) / 1e9,
                             "xcd_remap": not args.no_remap},

@@ -322,9 +322,9 @@ __device__ __forceinline__ void store_padded(const GatherRegs& g, const SampleAr
             const uint32_t s = (uint32_t)((it0 + i) * kWave + lane);
             const uint32_t ql = div_by(s, (uint32_t)f, f_magic);
             if (q0 + (int64_t)ql < Q) {
-                p.out_nbr[out0 + s] = g.nbr[i];
-                p.out_eid[out0 + s] = g.eid[i];
-                p.out_ts[out0 + s] = g.ts[i];
+                __builtin_nontemporal_store(g.nbr[i], &p.out_nbr[out0 + s]);
+                __builtin_nontemporal_store(g.eid[i], &p.out_eid[out0 + s]);
+                __builtin_nontemporal_store(g.ts[i], &p.out_ts[out0 + s]);
             }
         }
     }
@@ -397,8 +397,8 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
     w.tb = 0.0f;
     int32_t n_nodes = 0;
     if (q < Q) {
-        const int32_t v = p.targets[q];
-        w.te = p.t_end[q];
+        const int32_t v = __builtin_nontemporal_load(&p.targets[q]);
+        w.te = __builtin_nontemporal_load(&p.t_end[q]);
         w.tb = p.t_start ? p.t_start[q] : (p.delta == INFINITY ? -INFINITY : w.te - p.delta);
         int64_t nbase = 0;
         bool ok = (uint32_t)v < (uint64_t)p.num_nodes && !(w.te != w.te) && !(w.tb != w.tb);
@@ -629,7 +629,7 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
             store_padded(g, p, f_magic, lane, it0, q0, Q);
         }
     }
-    if (q < Q) p.out_count[q] = k;
+    if (q < Q) __builtin_nontemporal_store(k, &p.out_count[q]);
 }
 
 // ---- padding removal -------------------------------------------------------------------

@@ -30,6 +30,10 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--batch", type=int, default=0,
+                    help="first-hop queries: the last BATCH events of the stream (a training mini-batch, section 6: 600-4000 "
+                         "edges) instead of every event")
+    ap.add_argument("--graph", action="store_true", help="capture the call into a HIP graph once and time replays")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench_khop.py: one GPU only", file=sys.stderr)
@@ -51,15 +55,25 @@ def main() -> int:
         plan.add_edges_device(d_src[lo:hi], d_dst[lo:hi], d_ts[lo:hi])
     del d_dst
 
-    hops, ws = plan.run_khop(fanouts, d_src, None, d_ts)           # allocates the per-hop buffers once
+    q_src, q_ts, h_src, h_ts = d_src, d_ts, st.src, st.ts
+    if args.batch:
+        Q = min(args.batch, Q)
+        q_src, q_ts, h_src, h_ts = d_src[-Q:].contiguous(), d_ts[-Q:].contiguous(), st.src[-Q:], st.ts[-Q:]
+    hops, ws = plan.run_khop(fanouts, q_src, None, q_ts)           # allocates the per-hop buffers once
     torch.cuda.synchronize()
     p = lambda t: 0 if t is None else t.data_ptr()
     ptrs = [{k: p(v) for k, v in h.items() if k not in ("cap", "fanout")} for h in hops]
     stream = torch.cuda.current_stream().cuda_stream
 
     def step():
-        B.tns_run_khop(plan.handle, fanouts, float("inf"), Q, p(d_src), 0, p(d_ts), 0, 0, ptrs, ws.data_ptr(), ws.numel(), stream)
+        B.tns_run_khop(plan.handle, fanouts, float("inf"), Q, p(q_src), 0, p(q_ts), 0, 0, ptrs, ws.data_ptr(), ws.numel(),
+                       torch.cuda.current_stream().cuda_stream)
 
+    if args.graph:
+        eager, graph, side = step, torch.cuda.CUDAGraph(), torch.cuda.Stream()
+        with torch.cuda.graph(graph, stream=side):
+            eager()
+        step = graph.replay
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -77,7 +91,7 @@ def main() -> int:
     n_q = [Q]
     for h in hops[:-1]:
         n_q.append(int(h["rowptr"][n_q[-1]].item()))
-    alg, targets, t_end = 0, d_src, d_ts
+    alg, targets, t_end = 0, q_src, q_ts
     counters = torch.zeros(4, dtype=torch.int64, device=dev)
     for h, f, q in zip(hops, fanouts, n_q):
         plan.set_sampler(f, B.TNS_POLICY_RECENT, 0, 0)
@@ -95,7 +109,7 @@ def main() -> int:
         adj = oracle.Adjacency(st.num_nodes, st.src, st.dst, st.ts)
         k = min(Q, 1 << 22)
         t0 = time.perf_counter()
-        tg, te, done, ok = st.src[:k], st.ts[:k], 0, True
+        tg, te, done, ok = h_src[:k], h_ts[:k], 0, True
         for h, f in zip(hops, fanouts):
             ref = adj.sample(tg, None, te, f, policy=0, threads=16)
             rowptr, cn, ce, ct = oracle.compact(ref)
@@ -112,8 +126,10 @@ def main() -> int:
         "metric": "hot-path elements/sec over all hops at 1 MI355X", "value": total_q / (ms * 1e-3), "unit": "elements/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
         "dtype": "int32 ids / fp32 timestamps (copied and compared, no arithmetic)", "data": "synthetic",
-        "config": {"workload": f"{wl.name} recipe, n=2^{args.log2n}: one first-hop query per event, fan-outs {fanouts}, recent "
-                               "policy, unbounded window, hop h+1 = dense output of hop h", "queries_per_hop": n_q},
+        "config": {"workload": f"{wl.name} recipe, n=2^{args.log2n}: "
+                               + (f"first-hop queries = the last {Q} events" if args.batch else "one first-hop query per event")
+                               + f", fan-outs {fanouts}, recent policy, unbounded window, hop h+1 = dense output of hop h",
+                   "queries_per_hop": n_q, "hip_graph_replay": bool(args.graph)},
         "roofline": {"bound": "hbm", "achieved": alg / (ms_gpu * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
                      "frac": alg / (ms_gpu * 1e-3) / 1e9 / 8000.0, "traffic": None, "algorithmic_bytes_per_step": alg,
                      "ms_gpu_per_step": ms_gpu},

@@ -161,6 +161,40 @@ def test_standalone_compaction_equals_fused(B, oracle_lib):
     plan.close()
 
 
+def test_step_replayed_from_a_hip_graph(B, oracle_lib):
+    # tns_run only enqueues kernels (the chained scan's state is cleared by a kernel, not by a memset),
+    # so a step can be captured once and replayed; every replay is checked, with eager work in between
+    import torch
+    st = W.tiny_stream(91, 20000, 300, 2048, ties=True)
+    wl = wl_of(st, fanout=10)
+    dev = torch.device("cuda", 0)
+    d_t, d_e = torch.from_numpy(st.src).to(dev), torch.from_numpy(st.ts).to(dev)
+    for policy in (0, 1):
+        plan = build_plan(B, wl, policy, seed=5)
+        ref = oracle_sample(oracle_lib, wl, st.src, None, st.ts, None, 10, policy, 0, 5)
+        out = plan.alloc_outputs(st.n, compact=True)
+        plan.run(d_t, None, d_e, out=out)                      # eager once: loads the code objects
+        torch.cuda.synchronize()
+        graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+        with torch.cuda.graph(graph, stream=side):
+            plan.run(d_t, None, d_e, out=out)
+        for rep in range(3):
+            for name, t in out.items():
+                if name != "workspace":
+                    t.zero_()
+            assert float((d_e * 2).sum().item()) > 0          # unrelated eager work and a synchronisation
+            graph.replay()
+            torch.cuda.synchronize()
+            total = int(out["rowptr"][-1].item())
+            got = dict(nbr=out["nbr"].cpu().numpy().reshape(st.n, 10), eid=out["eid"].cpu().numpy().reshape(st.n, 10),
+                       ts=out["ts"].cpu().numpy().reshape(st.n, 10), count=out["count"].cpu().numpy(),
+                       rowptr=out["rowptr"].cpu().numpy(), cmp_nbr=out["cmp_nbr"][:total].cpu().numpy(),
+                       cmp_eid=out["cmp_eid"][:total].cpu().numpy(), cmp_ts=out["cmp_ts"][:total].cpu().numpy())
+            assert_same(got, ref, oracle_lib, f"policy={policy} replay {rep}")
+        del graph
+        plan.close()
+
+
 # ---- deletion (tombstones) -------------------------------------------------------------------------
 
 @pytest.mark.parametrize("policy", [0, 1])

@@ -762,6 +762,9 @@ hipError_t launch_sample_t(const SampleArgs& a, hipStream_t stream) {
     int32_t gshift = (POLICY == 0 && a.fanout <= kCoopGroup) ? 4 : -1;
     const size_t per_wave_all = per_wave + (gshift >= 0 ? (size_t)kWave * 16 : 0);
     int waves = (int)std::min<size_t>(FUSED ? 16 : 4, std::max<size_t>(1, (62u << 10) / per_wave_all));
+    // small batches: smaller workgroups, so that the queries spread over the compute units instead of
+    // queueing at the address units of a few
+    while (waves > 1 && (a.Q + (int64_t)waves * kWave - 1) / ((int64_t)waves * kWave) < 512) waves >>= 1;
     const int64_t per_wg = (int64_t)waves * kWave;
     const int64_t grid = (a.Q + per_wg - 1) / per_wg;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;

@@ -174,3 +174,13 @@ def test_tombstone_deletion_on_the_host():
     B.tns_delete_nodes(h, 0, [2])
     B.tns_delete_nodes(h, 0, [2], deleted=False)
     B.tns_destroy(h)
+
+
+@pytest.mark.parametrize("script", ["bench.py", "bench_cache.py", "bench_ingest.py", "bench_khop.py"])
+def test_benches_refuse_more_than_one_gpu(script):
+    # one GPU per box: no collectives, no sharding; the benches say so instead of running
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, script), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""

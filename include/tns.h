@@ -48,7 +48,8 @@ typedef enum {
     TNS_ERANGE = -3, /* source node id or instance outside the configured range            */
     TNS_ENOMEM = -4, /* host or device allocation failed                                   */
     TNS_EHIP = -5,   /* HIP runtime error (no device, launch failure, ...)                 */
-    TNS_ESTATE = -6, /* tns_run before the first tns_commit                                */
+    TNS_ESTATE = -6, /* tns_run before the first tns_commit; host batch for a device-built store
+                        or the reverse                                                      */
     TNS_ESIZE = -7   /* workspace too small, or a size beyond a documented limit           */
 } tns_status;
 
@@ -141,7 +142,9 @@ TNS_API int tns_add_edges_device(tns_plan *plan, int32_t instance, const int32_t
  * stored edges matched.  Edge ids must therefore be non-negative (tns_add_edges rejects negative
  * ids): the store marks a deleted edge by complementing its id.  Cost: a scan of the node's
  * edges per pair on the host; on the device, a query that meets a block holding deleted edges
- * checks that block's candidates one by one.
+ * checks that block's candidates one by one.  For a store built on the device
+ * (TNS_FLAG_DEVICE_INGEST) both calls copy the requests over, apply them with a kernel on the
+ * default stream and wait for it: they take effect at once, without tns_commit.
  *
  * tns_delete_nodes: HOST array of m node ids; a deleted node (deleted != 0) returns no neighbours
  * as a target; deleted = 0 restores it.  Edges that point TO a deleted node are not filtered:
@@ -155,7 +158,8 @@ TNS_API int tns_delete_nodes(tns_plan *plan, int32_t instance, const int32_t *no
  * Make everything ingested so far visible to tns_run: uploads the changed parts of the
  * node table, block records and edge data to the device (allocating or growing device
  * memory as needed) on `hip_stream` (a hipStream_t, NULL = default stream) and waits for
- * the upload.
+ * the upload.  For a store built on the device there is nothing to upload; the call only makes
+ * sure the (possibly empty) store exists.
  */
 TNS_API int tns_commit(tns_plan *plan, void *hip_stream);
 
@@ -189,6 +193,11 @@ TNS_API int tns_workspace(const tns_plan *plan, int64_t Q, size_t *bytes);
  *
  * TNS_ESTATE before the first commit, TNS_ESIZE for a short workspace, TNS_EINVAL for
  * missing pointers, TNS_EHIP if a launch fails.
+ *
+ * Recent policy with compaction: both steps run in one kernel whose workgroups pass their dense
+ * offsets along a chain; a workgroup waits for its predecessors for a bounded time only.  Should
+ * that bound ever be hit, the second 32-bit word of d_workspace is non-zero once the stream's
+ * work is done and the dense outputs are invalid (the padded ones are not affected).
  */
 TNS_API int tns_run(tns_plan *plan, int64_t Q, const int32_t *d_targets, const float *d_t_start,
             const float *d_t_end, const int64_t *d_inst_rowptr, int64_t query_id_base,
@@ -255,8 +264,9 @@ TNS_API int tns_traffic_model(tns_plan *plan, int64_t Q, const int32_t *d_target
  * Layout figures of one instance (the columns of the block-sizing table in section 6.2):
  * average and maximum block-list length, bytes of edge data (all slots) and of metadata
  * (node table + block records) as stored on the device, number of unfilled edge slots,
- * number of blocks and of stored edges.  Any output pointer may be NULL.  instance = -1
- * sums over all instances.
+ * number of blocks and of stored edges.  instance = -1 sums over all instances.  For a store
+ * built on the device the longest list is reduced by a kernel on the default stream (the call
+ * waits for it).
  */
 typedef struct {
     double avg_list_len;
@@ -270,8 +280,9 @@ typedef struct {
 TNS_API int tns_stats(const tns_plan *plan, int32_t instance, tns_stats_t *out);
 
 /*
- * Inspection of the host-side layout (for tests): the blocks of node `node` of `instance`
- * from the oldest to the newest.  Arrays are HOST with room for `max_blocks` entries (any
+ * Inspection of the layout (for tests): the blocks of node `node` of `instance` from the
+ * oldest to the newest, from the host builder's copy or, for a store built on the device, read
+ * back from device memory.  Arrays are HOST with room for `max_blocks` entries (any
  * may be NULL); returns the node's block count (which may exceed max_blocks) or a negative
  * status.
  */

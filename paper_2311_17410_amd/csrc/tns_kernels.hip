@@ -350,6 +350,8 @@ __device__ __forceinline__ void store_dense(const GatherRegs& g, const SampleArg
     }
 }
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
 __device__ __forceinline__ BlockRec as_rec(const uint4& u) {
     BlockRec r;
     r.t_min = __uint_as_float(u.x);
@@ -362,8 +364,12 @@ __device__ __forceinline__ BlockRec as_rec(const uint4& u) {
 // FUSED: also removes the padding in the same pass (rowptr and dense arrays), with the tile
 // offsets obtained from a chained scan over the workgroups.
 template <int POLICY, bool INCL, typename pos_t, bool COUNT, bool FUSED>
-__global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const SampleArgs p, const int32_t stride,
-                                                                          const uint32_t f_magic, const int32_t gshift) {
+__global__ void __launch_bounds__(FUSED ? 1024 : 256, FUSED ? 4 : 6) tns_sample_kernel(const SampleArgs p, const int32_t stride,
+                                                                          const uint32_t f_magic, const int32_t gshift,
+                                                                          const uint32_t chunk) {
+    // LDS: one chunk per wave.  First the staging area of the node lines (3 KiB), later, in the same bytes,
+    // the wave's rows of selected positions and, behind them, the descriptors of the cooperative search.
+    constexpr bool COOP_NODE = !COUNT;
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int64_t s_tile_base;
     __shared__ int32_t s_wave_sum[16];
@@ -390,12 +396,14 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
 
     Walk<POLICY, INCL, pos_t> w;
     w.f = f;
-    w.s_pos = reinterpret_cast<pos_t*>(smem) + (size_t)wave * kWave * stride + (size_t)lane * stride;
+    unsigned char* const my_lds = smem + (size_t)wave * chunk;
+    w.s_pos = reinterpret_cast<pos_t*>(my_lds) + (size_t)lane * stride;
     w.edges = p.edges;
     w.group = (POLICY == 0 && gshift >= 0) ? (1 << gshift) : 0;
     w.te = 0.0f;
     w.tb = 0.0f;
     int32_t n_nodes = 0;
+    int64_t nidx = -1;           // index of the target's entry in the node table, -1: no walk
     if (q < Q) {
         const int32_t v = __builtin_nontemporal_load(&p.targets[q]);
         w.te = __builtin_nontemporal_load(&p.t_end[q]);
@@ -412,16 +420,61 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
             ok = ok && lo < p.num_instances;
             nbase = (int64_t)lo * p.num_nodes;
         }
-        if (ok) {
-            // the node's 128-byte line: header + the records of up to 7 blocks, newest first
-            const uint4* __restrict__ line = reinterpret_cast<const uint4*>(p.nodes + (nbase + v));
-            const uint4 h = line[0];
-            ++n_nodes;
-            const int32_t nb = (h.w & 1) ? 0 : (int32_t)h.x;      // deleted node: no blocks
-            if (nb > 0 && nb <= kInlineBlocks) {
-                uint4 L[kInlineBlocks];
+        if (ok) nidx = nbase + v;
+    }
+    // the node's 128-byte line: header + the records of up to 7 blocks, newest first
+    uint4 hd = make_uint4(0u, 0u, 0u, 0u);
+    uint4 L[kInlineBlocks];
+    if (COOP_NODE) {
+        // Eight lanes fetch one query's line with one instruction (16 bytes each), eight queries per
+        // instruction; the pieces reach their owner through LDS.  One request per line lets the loads
+        // carry the non-temporal hint: a node line is used once and should not push edge lines out
+        // of the L2.
+        unsigned char* stage = my_lds;
+        const int piece = lane & 7, sub = lane >> 3;
+        u32x4 R[8];
 #pragma unroll
-                for (int j = 0; j < kInlineBlocks; ++j) L[j] = line[1 + j];
+        for (int i = 0; i < 8; ++i) {
+            const int64_t src = shfl64(nidx, i * 8 + sub);
+            R[i] = u32x4{0u, 0u, 0u, 0u};
+            if (src >= 0) R[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p.nodes + src) + piece);
+        }
+        u32x4 P[8];
+        // through LDS in three rounds of 24, 24 and 16 queries (3 KiB of staging); 16-byte pieces are
+        // swizzled by the query number so that neither the writes nor the reads collide on banks
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                if (r * 3 + i < 8) {
+                    const int ql = i * 8 + sub;             // query within the round
+                    *reinterpret_cast<u32x4*>(stage + ql * 128 + ((piece ^ (ql & 7)) << 4)) = R[(r * 3 + i) & 7];
+                }
+            }
+            wave_lds_sync();
+            const int ql = lane - r * 24;
+            if (ql >= 0 && ql < 24) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) P[j] = *reinterpret_cast<const u32x4*>(stage + ql * 128 + ((j ^ (ql & 7)) << 4));
+            }
+            wave_lds_sync();
+        }
+        hd = make_uint4(P[0].x, P[0].y, P[0].z, P[0].w);
+#pragma unroll
+        for (int j = 0; j < kInlineBlocks; ++j) L[j] = make_uint4(P[1 + j].x, P[1 + j].y, P[1 + j].z, P[1 + j].w);
+    } else if (nidx >= 0) {
+        // all eight 16-byte pieces are requested at once: the records are needed right after the
+        // header for all but empty nodes and long lists
+        const uint4* __restrict__ line = reinterpret_cast<const uint4*>(p.nodes + nidx);
+        hd = line[0];
+#pragma unroll
+        for (int j = 0; j < kInlineBlocks; ++j) L[j] = line[1 + j];
+    }
+    if (nidx >= 0) {
+        {
+            ++n_nodes;
+            const int32_t nb = (hd.w & 1) ? 0 : (int32_t)hd.x;      // deleted node: no blocks
+            if (nb > 0 && nb <= kInlineBlocks) {
                 bool go = true;
 #pragma unroll
                 for (int j = 0; j < kInlineBlocks; ++j)
@@ -435,8 +488,8 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
                 }
             } else if (nb > kInlineBlocks) {
                 // long list: all records of the node, oldest first, in one run of the directory
-                const int64_t d0 = (int64_t)h.z * kDirAlign;
-                if (POLICY == 1 && d0 + nb <= p.num_dir && !(h.w & 2)) {
+                const int64_t d0 = (int64_t)hd.z * kDirAlign;
+                if (POLICY == 1 && d0 + nb <= p.num_dir && !(hd.w & 2)) {
                     // Uniform policy on a long list without deleted edges: the node's edges, blocks
                     // concatenated, form one chronological sequence and the candidates are a contiguous
                     // range [L, R) of it.  With the number of edges before each block kept next to the
@@ -510,12 +563,12 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
     int32_t h = 0;               // edges of the searched block that lie before the window end
     if (POLICY == 0 && gshift >= 0) {
         constexpr int G = kCoopGroup, groups = kWave / G;
-        unsigned char* extra = smem + (size_t)waves_per_wg * kWave * stride * sizeof(pos_t);
+        unsigned char* extra = my_lds + (size_t)kWave * stride * sizeof(pos_t);
         // per query: window start (40-bit slot index) with the window size in the upper bits,
         // the window end time, and the result
-        uint2* s_q = reinterpret_cast<uint2*>(extra) + wave * kWave;
-        float* s_te = reinterpret_cast<float*>(extra + (size_t)waves_per_wg * kWave * sizeof(uint2)) + wave * kWave;
-        int32_t* s_h = reinterpret_cast<int32_t*>(extra + (size_t)waves_per_wg * kWave * (sizeof(uint2) + sizeof(float))) + wave * kWave;
+        uint2* s_q = reinterpret_cast<uint2*>(extra);
+        float* s_te = reinterpret_cast<float*>(extra + (size_t)kWave * sizeof(uint2));
+        int32_t* s_h = reinterpret_cast<int32_t*>(extra + (size_t)kWave * (sizeof(uint2) + sizeof(float)));
         const int64_t win0 = w.d_off + w.d_lo;
         s_q[lane] = make_uint2((uint32_t)(win0 & 0xffffffffll), ((uint32_t)(win0 >> 32) & 0xffu) | ((uint32_t)w.d_n << 8));
         s_te[lane] = w.te;
@@ -562,7 +615,7 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256) tns_sample_kernel(const Sa
         }
         return;
     }
-    const pos_t* __restrict__ w_pos = reinterpret_cast<const pos_t*>(smem) + (size_t)wave * kWave * stride;
+    const pos_t* __restrict__ w_pos = reinterpret_cast<const pos_t*>(my_lds);
 
     if (FUSED) {
         // Chained scan over the workgroup tiles for the dense offsets.
@@ -760,8 +813,9 @@ hipError_t launch_sample_t(const SampleArgs& a, hipStream_t stream) {
     // recent policy with fan-out <= 16: the wave finishes the in-block searches together
     // (16 more bytes of LDS per query); otherwise each lane searches alone
     int32_t gshift = (POLICY == 0 && a.fanout <= kCoopGroup) ? 4 : -1;
-    const size_t per_wave_all = per_wave + (gshift >= 0 ? (size_t)kWave * 16 : 0);
-    int waves = (int)std::min<size_t>(FUSED ? 16 : 4, std::max<size_t>(1, (62u << 10) / per_wave_all));
+    // per wave: position rows + search descriptors, and at least the 3 KiB in which the node lines are staged first
+    const size_t chunk = std::max<size_t>(per_wave + (gshift >= 0 ? (size_t)kWave * 16 : 0), COUNT ? 0 : 3072);
+    int waves = (int)std::min<size_t>(FUSED ? 16 : 4, std::max<size_t>(1, (62u << 10) / chunk));
     // small batches: smaller workgroups, so that the queries spread over the compute units instead of
     // queueing at the address units of a few
     while (waves > 1 && (a.Q + (int64_t)waves * kWave - 1) / ((int64_t)waves * kWave) < 512) waves >>= 1;
@@ -774,9 +828,9 @@ hipError_t launch_sample_t(const SampleArgs& a, hipStream_t stream) {
                            grid, a.rowptr, a.Q, a.Q_dev, a.total_out);
     }
     if (grid <= 0) return hipGetLastError();
-    const size_t lds = per_wave_all * waves;
+    const size_t lds = chunk * waves;
     hipLaunchKernelGGL((tns_sample_kernel<POLICY, INCL, pos_t, COUNT, FUSED>), dim3((unsigned)grid), dim3(waves * kWave),
-                       lds, stream, a, stride, magic_for(a.fanout), gshift);
+                       lds, stream, a, stride, magic_for(a.fanout), gshift, (uint32_t)chunk);
     return hipGetLastError();
 }
 

@@ -373,6 +373,7 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256, FUSED ? 4 : 6) tns_sample_
     extern __shared__ __align__(16) unsigned char smem[];
     __shared__ int64_t s_tile_base;
     __shared__ int32_t s_wave_sum[16];
+    __shared__ int32_t s_arrived;      // fused: waves of the tile that have finished their searches
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
     const int waves_per_wg = blockDim.x >> 6;
@@ -381,7 +382,10 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256, FUSED ? 4 : 6) tns_sample_
     if (FUSED) {
         // tiles are numbered in the order workgroups start
         ScanWorkspace* ws = static_cast<ScanWorkspace*>(p.scan_ws);
-        if (threadIdx.x == 0) s_tile_base = (int64_t)atomicAdd(&ws->ticket, 1u);
+        if (threadIdx.x == 0) {
+            s_tile_base = (int64_t)atomicAdd(&ws->ticket, 1u);
+            s_arrived = 0;
+        }
         __syncthreads();
         tile = s_tile_base;
         __syncthreads();
@@ -621,18 +625,12 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256, FUSED ? 4 : 6) tns_sample_
         // Chained scan over the workgroup tiles for the dense offsets.
         ScanWorkspace* ws = static_cast<ScanWorkspace*>(p.scan_ws);
         const int32_t inc = wave_inclusive_scan(k, lane);
-        if (lane == kWave - 1) s_wave_sum[wave] = inc;
-        __syncthreads();
-        int32_t wave_off = 0, wg_total = 0;
-        for (int i = 0; i < waves_per_wg; ++i) {
-            const int32_t t = s_wave_sum[i];
-            if (i < wave) wave_off += t;
-            wg_total += t;
-        }
-        // the tile total is published at once, so that later tiles can look past this one
-        if (wave == 0 && lane == 0 && tile > 0)
-            __hip_atomic_store(&ws->status[tile], kStTotal | (uint64_t)wg_total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        auto chain = [&]() {      // wave 0: look back for the tile's offset, publish the prefix
+        auto publish_total = [&](int32_t wg_total) {
+            // the tile total is published at once, so that later tiles can look past this one
+            if (lane == 0 && tile > 0)
+                __hip_atomic_store(&ws->status[tile], kStTotal | (uint64_t)wg_total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        };
+        auto chain = [&](int32_t wg_total) {      // one wave: look back for the tile's offset, publish the prefix
             const int64_t excl = tile > 0 ? lookback_exclusive(ws, tile, lane) : 0;
             if (lane == 0) {
                 __hip_atomic_store(&ws->status[tile], kStPrefix | (uint64_t)(excl + wg_total), __ATOMIC_RELAXED,
@@ -649,24 +647,52 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256, FUSED ? 4 : 6) tns_sample_
                 }
             }
         };
+        auto offset_of_wave = [&]() {
+            int32_t off = 0;
+            for (int i = 0; i < wave; ++i) off += s_wave_sum[i];
+            return off;
+        };
         GatherRegs g;
         if (f <= kGatherChunk) {
-            // Every wave first gathers (one batch of loads) and writes its padded rows; the gathered
-            // edges stay in registers.  Wave 0 then looks back for the tile offset (the earlier
-            // tiles have had the time of a gather to publish their totals), and only the dense
-            // copy waits for it.
+            // No barrier between a wave's searches and its gather (the lines the searches fetched are
+            // then still in the L2): the waves count themselves in, and the one that arrives last
+            // adds up the tile total and publishes it.  Every wave gathers (one batch of loads) and
+            // writes its padded rows, the gathered edges stay in registers; the last wave then looks
+            // back for the tile's offset (the earlier tiles have had the time of a gather to publish
+            // their totals), and only the dense copy waits for it.
+            int is_last = 0;
+            if (lane == kWave - 1) {
+                s_wave_sum[wave] = inc;
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                is_last = __hip_atomic_fetch_add(&s_arrived, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) == waves_per_wg - 1;
+            }
+            is_last = __shfl(is_last, kWave - 1, kWave);
+            int32_t wg_total = 0;
+            if (is_last) {
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                for (int i = 0; i < waves_per_wg; ++i) wg_total += s_wave_sum[i];
+                publish_total(wg_total);
+            }
+            wave_lds_sync();      // the positions were written by this wave's own lanes
             gather_load(g, p, f_magic, stride, w_pos, lane, 0, k);
             store_padded(g, p, f_magic, lane, 0, q0, Q);
-            if (wave == 0) chain();
+            if (is_last) chain(wg_total);
             __syncthreads();
-            const int64_t row = s_tile_base + wave_off + (inc - k);
+            const int64_t row = s_tile_base + offset_of_wave() + (inc - k);
             write_rowptr(row);
             store_dense(g, p, f_magic, lane, 0, row);
         } else {
             // larger fan-outs: offset first, then gather in batches and write both
-            if (wave == 0) chain();
+            if (lane == kWave - 1) s_wave_sum[wave] = inc;
             __syncthreads();
-            const int64_t row = s_tile_base + wave_off + (inc - k);
+            int32_t wg_total = 0;
+            for (int i = 0; i < waves_per_wg; ++i) wg_total += s_wave_sum[i];
+            if (wave == 0) {
+                publish_total(wg_total);
+                chain(wg_total);
+            }
+            __syncthreads();
+            const int64_t row = s_tile_base + offset_of_wave() + (inc - k);
             write_rowptr(row);
             for (int32_t it0 = 0; it0 < f; it0 += kGatherChunk) {
                 gather_load(g, p, f_magic, stride, w_pos, lane, it0, k);

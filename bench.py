@@ -195,8 +195,7 @@ def main() -> int:
     # The step: ONE tns_run with the dense outputs requested = sampling kernel with the padding
     # removal fused in (plus a tiny kernel that clears the chained scan's tile states).
     dense_write = 12 * n_edges + 8 * (Q + 1)
-    # uniform policy: tns_run keeps the two steps apart (sampling kernel, then the compaction kernels)
-    alg_step = alg_sample + dense_write if args.policy == "recent" else alg_sample + alg_compact
+    alg_step = alg_sample + dense_write
     log(f"warm-up {args.warmup}, timing {args.steps} steps")
     for _ in range(args.warmup):
         fused()
@@ -211,7 +210,7 @@ def main() -> int:
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     ms_kernel = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
-    assert args.policy != "recent" or int(out["workspace"][4:8].view(torch.int32).item()) == 0, "chained scan timed out"
+    assert int(out["workspace"][4:8].view(torch.int32).item()) == 0, "chained scan timed out"
 
     # for comparison, the same work as two steps: padded sampling, then stand-alone padding removal
     ev2 = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
@@ -261,7 +260,7 @@ def main() -> int:
                                f"policy={args.policy}, window={'0.25 span' if args.windowed else 'unbounded'}",
                    "queries": Q, "instances": wl.num_instances, "nodes_per_instance": wl.num_nodes,
                    "placement": args.placement, "ingest": args.ingest},
-        "roofline": {"bound": "hbm", "kernel": "tns_sample_kernel (padding removal fused)" if args.policy == "recent" else "tns_sample_kernel + tns_compact kernels (whole step)", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": "tns_sample_kernel (padding removal fused)", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "moved": moved, "copy_ceiling_GBs": copy_gbs,
                      "algorithmic_bytes_per_launch": alg_step, "bytes_breakdown": bytes_step,

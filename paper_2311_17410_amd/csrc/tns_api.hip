@@ -540,12 +540,8 @@ int tns_run(tns_plan* plan, int64_t Q, const int32_t* d_targets, const float* d_
     a.out_eid = d_out_eid;
     a.out_ts = d_out_ts;
     a.out_count = d_out_count;
-    // Recent policy: one pass, sampling with the padding removal fused in.  Uniform policy: the
-    // walk lengths differ much more between tiles, which makes the fused kernel's chained scan
-    // wait longer than a second pass over the padded rows costs (measured on C5: 48 ms fused,
-    // 42 ms in two steps), so the two steps are kept apart there.
-    const bool fuse = want_cmp && plan->cfg.policy == TNS_POLICY_RECENT;
-    if (fuse) {
+    if (want_cmp) {
+        // one pass: sampling with the padding removal fused in
         a.scan_ws = d_workspace;
         a.rowptr = d_rowptr;
         a.cmp_nbr = d_cmp_nbr;
@@ -554,9 +550,6 @@ int tns_run(tns_plan* plan, int64_t Q, const int32_t* d_targets, const float* d_
     }
     const hipError_t e = tns::launch_sample(a, stream);
     if (e != hipSuccess) return fail_hip(e, "launching the sampling kernel");
-    if (want_cmp && !fuse)
-        return run_compact(plan, Q, d_out_nbr, d_out_eid, d_out_ts, d_out_count, d_rowptr, d_cmp_nbr, d_cmp_eid,
-                           d_cmp_ts, d_workspace, stream);
     return TNS_OK;
 }
 
@@ -622,7 +615,6 @@ int tns_run_khop(tns_plan* plan, int32_t num_hops, const int32_t* fanouts, float
     const int32_t I = plan->cfg.num_instances;
     int64_t* header = static_cast<int64_t*>(d_workspace);
     void* scan_ws = static_cast<unsigned char*>(d_workspace) + khop_header_bytes(num_hops, I);
-    const bool fuse = plan->cfg.policy == TNS_POLICY_RECENT;
 
     for (int h = 0; h < num_hops; ++h) {
         const tns_hop_buffers& b = hops[h];
@@ -635,26 +627,13 @@ int tns_run_khop(tns_plan* plan, int32_t num_hops, const int32_t* fanouts, float
         a.out_ts = b.ts;
         a.out_count = b.count;
         a.total_out = total;
-        a.scan_ws = nullptr;
-        if (fuse) {
-            a.scan_ws = scan_ws;
-            a.rowptr = b.rowptr;
-            a.cmp_nbr = b.cmp_nbr;
-            a.cmp_eid = b.cmp_eid;
-            a.cmp_ts = b.cmp_ts;
-        }
+        a.scan_ws = scan_ws;                                    // sampling with the padding removal fused in
+        a.rowptr = b.rowptr;
+        a.cmp_nbr = b.cmp_nbr;
+        a.cmp_eid = b.cmp_eid;
+        a.cmp_ts = b.cmp_ts;
         hipError_t e = tns::launch_sample(a, stream);
         if (e != hipSuccess) return fail_hip(e, "launching the sampling kernel of a hop");
-        if (!fuse) {
-            tns::CompactArgs c{};
-            c.nbr = b.nbr; c.eid = b.eid; c.ts = b.ts; c.count = b.count;
-            c.rowptr = b.rowptr; c.cmp_nbr = b.cmp_nbr; c.cmp_eid = b.cmp_eid; c.cmp_ts = b.cmp_ts;
-            c.Q = caps[h]; c.Q_dev = a.Q_dev; c.total_out = total;
-            c.fanout = fanouts[h];
-            c.workspace = scan_ws;
-            e = tns::launch_compact(c, stream);
-            if (e != hipSuccess) return fail_hip(e, "launching the compaction kernels of a hop");
-        }
         if (h + 1 == num_hops) break;
         // queries of the next hop: the dense entries of this one
         if (a.inst_rowptr) {

@@ -834,14 +834,17 @@ template <int POLICY, bool INCL, typename pos_t, bool COUNT, bool FUSED>
 hipError_t launch_sample_t(const SampleArgs& a, hipStream_t stream) {
     const int32_t stride = a.fanout | 1;                                    // odd: conflict-free per-lane rows
     const size_t per_wave = (size_t)kWave * stride * sizeof(pos_t);
-    // The fused variant uses large workgroups: one chained-scan step per 1024 queries keeps the
-    // rate at which tiles publish their totals low enough for the look-back to keep up.
+    // The fused variant uses large workgroups under the recent policy: one chained-scan step per 1024
+    // queries keeps the rate at which tiles publish their totals low enough for the look-back to keep
+    // up.  Under the uniform policy the waves of a tile finish far apart (two walks, per-lane searches)
+    // and wait for each other before the dense copy, so small tiles win there (C5: 36.5 ms with 16
+    // waves, 32.6 with 8, 31.3 with 4, 34.1 with 2).
     // recent policy with fan-out <= 16: the wave finishes the in-block searches together
     // (16 more bytes of LDS per query); otherwise each lane searches alone
     int32_t gshift = (POLICY == 0 && a.fanout <= kCoopGroup) ? 4 : -1;
     // per wave: position rows + search descriptors, and at least the 3 KiB in which the node lines are staged first
     const size_t chunk = std::max<size_t>(per_wave + (gshift >= 0 ? (size_t)kWave * 16 : 0), COUNT ? 0 : 3072);
-    int waves = (int)std::min<size_t>(FUSED ? 16 : 4, std::max<size_t>(1, (62u << 10) / chunk));
+    int waves = (int)std::min<size_t>(FUSED ? (POLICY == 1 ? 4 : 16) : 4, std::max<size_t>(1, (62u << 10) / chunk));
     // small batches: smaller workgroups, so that the queries spread over the compute units instead of
     // queueing at the address units of a few
     while (waves > 1 && (a.Q + (int64_t)waves * kWave - 1) / ((int64_t)waves * kWave) < 512) waves >>= 1;

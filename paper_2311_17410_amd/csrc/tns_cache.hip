@@ -94,6 +94,8 @@ __global__ void __launch_bounds__(256) k_lookup(CacheState c, int policy, int64_
     }
 }
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
 // out[b] = cached row or row of the backing store; VEC floats per thread, rows stay coalesced
 template <int VEC>
 __global__ void __launch_bounds__(256) k_gather(const float* __restrict__ rows, const float* __restrict__ store, int32_t dim,
@@ -105,16 +107,18 @@ __global__ void __launch_bounds__(256) k_gather(const float* __restrict__ rows, 
     const int64_t b = t / per_row;
     const int32_t col = (int32_t)(t - b * per_row) * VEC;
     const int32_t s = slots[b];
+    // the output and the rows of the backing store are touched once (non-temporal); the cached rows are
+    // what should stay in the L2
     if (VEC == 4) {
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (s >= 0) v = *reinterpret_cast<const float4*>(rows + (int64_t)s * dim + col);
-        else if (s == -1) v = *reinterpret_cast<const float4*>(store + (int64_t)ids[b] * dim + col);
-        *reinterpret_cast<float4*>(out + b * dim + col) = v;
+        f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+        if (s >= 0) v = *reinterpret_cast<const f32x4*>(rows + (int64_t)s * dim + col);
+        else if (s == -1) v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(store + (int64_t)ids[b] * dim + col));
+        __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(out + b * dim + col));
     } else {
         float v = 0.f;
         if (s >= 0) v = rows[(int64_t)s * dim + col];
-        else if (s == -1) v = store[(int64_t)ids[b] * dim + col];
-        out[b * dim + col] = v;
+        else if (s == -1) v = __builtin_nontemporal_load(store + (int64_t)ids[b] * dim + col);
+        __builtin_nontemporal_store(v, out + b * dim + col);
     }
 }
 

@@ -131,15 +131,10 @@ __global__ void __launch_bounds__(256) k_lru_scores(int32_t* __restrict__ score,
     }
 }
 
-// flag[b] = 1 for the first occurrence of each missed id
-__global__ void __launch_bounds__(256) k_mark_first(const int32_t* __restrict__ first_idx, int64_t B,
-                                                    const int32_t* __restrict__ ids, const int32_t* __restrict__ slots,
-                                                    int32_t* __restrict__ flag) {
-    const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (b < B) flag[b] = (slots[b] == -1 && first_idx[ids[b]] == (int32_t)b) ? 1 : 0;
-}
-
-// ---- exclusive scan of an int32 array, in place (three kernels) ------------------------------
+// ---- compaction of flagged elements in three launches -------------------------------------------
+// A flag functor gives each element a packed 64-bit count (one or two counters); (1) per-tile sums,
+// (2) exclusive scan of the tile sums by one workgroup, (3) per tile: the flags again, a local scan,
+// and the functor's emit() with the number of flagged elements before each one.  No flag array.
 
 __device__ __forceinline__ int32_t wave_inclusive_scan(int32_t v, int lane) {
 #pragma unroll
@@ -149,93 +144,106 @@ __device__ __forceinline__ int32_t wave_inclusive_scan(int32_t v, int lane) {
     }
     return v;
 }
-
-__global__ void __launch_bounds__(256) k_scan_tile_sums(const int32_t* __restrict__ a, int64_t n, int32_t* __restrict__ sums) {
-    __shared__ int32_t s_w[4];
-    const int64_t base = (int64_t)blockIdx.x * kScanTile;
-    int32_t v = 0;
+__device__ __forceinline__ int64_t wave_inclusive_scan64(int64_t v, int lane) {
 #pragma unroll
-    for (int i = 0; i < kScanTile / 256; ++i) {
-        const int64_t k = base + i * 256 + threadIdx.x;
-        if (k < n) v += a[k];
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int64_t u = (int64_t)__shfl_up((long long)v, d, kWave);
+        if (lane >= d) v += u;
     }
+    return v;
+}
+
+constexpr int kPerThread = kScanTile / 256;
+
+template <class F>
+__global__ void __launch_bounds__(256) k_flag_tile_sums(const F f, int64_t n, int64_t* __restrict__ sums) {
+    __shared__ int64_t s_w[4];
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kPerThread;
+    int64_t v = 0;
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i)
+        if (base + i < n) v += f.count(base + i);
     const int lane = threadIdx.x & 63;
-    v = wave_inclusive_scan(v, lane);
+    v = wave_inclusive_scan64(v, lane);
     if (lane == 63) s_w[threadIdx.x >> 6] = v;
     __syncthreads();
     if (threadIdx.x == 0) sums[blockIdx.x] = s_w[0] + s_w[1] + s_w[2] + s_w[3];
 }
 
-// one workgroup: exclusive scan of the tile sums; total -> *total
-__global__ void __launch_bounds__(1024) k_scan_sums(int32_t* __restrict__ sums, int64_t num_tiles, int32_t* __restrict__ total) {
-    __shared__ int32_t s_w[16];
-    __shared__ int32_t s_carry;
+// one workgroup: exclusive scan of the tile sums in place; the functor receives the total
+template <class F>
+__global__ void __launch_bounds__(1024) k_flag_scan_sums(const F f, int64_t* __restrict__ sums, int64_t num_tiles) {
+    __shared__ int64_t s_w[16];
+    __shared__ int64_t s_carry;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (threadIdx.x == 0) s_carry = 0;
     __syncthreads();
     for (int64_t base = 0; base < num_tiles; base += 1024) {
         const int64_t i = base + threadIdx.x;
-        const int32_t v = i < num_tiles ? sums[i] : 0;
-        const int32_t inc = wave_inclusive_scan(v, lane);
+        const int64_t v = i < num_tiles ? sums[i] : 0;
+        const int64_t inc = wave_inclusive_scan64(v, lane);
         if (lane == 63) s_w[wave] = inc;
         __syncthreads();
-        int32_t wave_off = 0, all = 0;
+        int64_t wave_off = 0, all = 0;
 #pragma unroll
         for (int w = 0; w < 16; ++w) {
-            const int32_t t = s_w[w];
+            const int64_t t = s_w[w];
             if (w < wave) wave_off += t;
             all += t;
         }
-        const int32_t carry = s_carry;
+        const int64_t carry = s_carry;
         if (i < num_tiles) sums[i] = carry + wave_off + (inc - v);
         __syncthreads();
         if (threadIdx.x == 0) s_carry = carry + all;
         __syncthreads();
     }
-    if (threadIdx.x == 0) *total = s_carry;
+    if (threadIdx.x == 0) f.total(s_carry);
 }
 
-__global__ void __launch_bounds__(256) k_scan_apply(int32_t* __restrict__ a, int64_t n, const int32_t* __restrict__ sums) {
-    __shared__ int32_t s_w[4];
-    constexpr int kPer = kScanTile / 256;
-    const int64_t base = (int64_t)blockIdx.x * kScanTile;
+template <class F>
+__global__ void __launch_bounds__(256) k_flag_collect(const F f, int64_t n, const int64_t* __restrict__ sums) {
+    __shared__ int64_t s_w[4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int32_t c[kPer], sum = 0;
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kPerThread;
+    int64_t c[kPerThread], sum = 0;
 #pragma unroll
-    for (int i = 0; i < kPer; ++i) {
-        const int64_t k = base + threadIdx.x * kPer + i;
-        c[i] = k < n ? a[k] : 0;
+    for (int i = 0; i < kPerThread; ++i) {
+        c[i] = base + i < n ? f.count(base + i) : 0;
         sum += c[i];
     }
-    const int32_t inc = wave_inclusive_scan(sum, lane);
+    const int64_t inc = wave_inclusive_scan64(sum, lane);
     if (lane == 63) s_w[wave] = inc;
     __syncthreads();
-    int32_t excl = sums[blockIdx.x] + inc - sum;
-    for (int w = 0; w < wave; ++w) excl += s_w[w];
+    int64_t before = sums[blockIdx.x] + inc - sum;
+    for (int w = 0; w < wave; ++w) before += s_w[w];
 #pragma unroll
-    for (int i = 0; i < kPer; ++i) {
-        const int64_t k = base + threadIdx.x * kPer + i;
-        if (k < n) a[k] = excl;
-        excl += c[i];
+    for (int i = 0; i < kPerThread; ++i) {
+        if (c[i]) f.emit(base + i, before);
+        before += c[i];
     }
 }
 
-// new_ids[pos] = id for the first occurrences (pos = scanned flag), up to max_replace of them;
-// every missed row clears its id's scratch entry; m = min(distinct misses, max_replace)
-__global__ void __launch_bounds__(256) k_collect_new(int32_t* __restrict__ first_idx, int64_t B, const int32_t* __restrict__ ids,
-                                                     const int32_t* __restrict__ slots, const int32_t* __restrict__ pos,
-                                                     int32_t max_replace, int32_t* __restrict__ new_ids, Ctl* ctl) {
-    const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (b == 0) {
-        const int32_t m = min(ctl->n_unique, max_replace);
+// Distinct missed ids in the order of their first occurrence (the flag: a missed row that is the first
+// of its id), up to max_replace of them; the total fixes how many entries this update replaces.
+struct NewIds {
+    const int32_t* first_idx;
+    const int32_t* ids;
+    const int32_t* slots;
+    int32_t max_replace;
+    int32_t* new_ids;
+    Ctl* ctl;
+    __device__ int64_t count(int64_t b) const { return slots[b] == -1 && first_idx[ids[b]] == (int32_t)b ? 1 : 0; }
+    __device__ void emit(int64_t b, int64_t before) const {
+        if (before < max_replace) new_ids[before] = ids[b];
+    }
+    __device__ void total(int64_t n_unique) const {
+        const int32_t m = (int32_t)(n_unique < max_replace ? n_unique : max_replace);
+        ctl->n_unique = (int32_t)n_unique;
         ctl->m = m;
         ctl->remaining = m;
     }
-    if (b < B && slots[b] == -1) {
-        const int32_t id = ids[b];
-        if (first_idx[id] == (int32_t)b && pos[b] < max_replace) new_ids[pos[b]] = id;
-    }
-}
+};
+
 __global__ void __launch_bounds__(256) k_clear_first(int32_t* __restrict__ first_idx, int64_t B, const int32_t* __restrict__ ids,
                                                      const int32_t* __restrict__ slots) {
     const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -246,69 +254,75 @@ __global__ void __launch_bounds__(256) k_clear_first(int32_t* __restrict__ first
 
 __device__ __forceinline__ uint32_t score_key(int32_t score) { return (uint32_t)score ^ 0x80000000u; }   // unsigned order = signed order
 
-// histogram of one 8-bit digit over the entries whose decided high bits match
-__global__ void __launch_bounds__(256) k_select_hist(const int32_t* __restrict__ score, int64_t capacity, int shift, Ctl* ctl) {
+// One pass of the radix select (8 bits, most significant first), two launches.  First the histogram of
+// the digit over the entries whose decided high bits match.  LRU_UPDATE (first pass under LRU): the scores
+// are brought up to date on the way (every score decremented, entries accessed by the batch reset to 0).
+template <bool LRU_UPDATE>
+__global__ void __launch_bounds__(256) k_select_hist(int32_t* __restrict__ score, int32_t* __restrict__ touched, int64_t capacity,
+                                                     int shift, Ctl* ctl) {
     __shared__ int32_t s_h[256];
-    if (ctl->m == 0) return;
+    const bool active = ctl->m > 0;
+    if (!LRU_UPDATE && !active) return;
     s_h[threadIdx.x] = 0;
     __syncthreads();
     const uint32_t prefix = ctl->prefix, mask = ctl->mask;
     for (int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x; s < capacity; s += (int64_t)gridDim.x * 256) {
-        const uint32_t k = score_key(score[s]);
-        if ((k & mask) == prefix) atomicAdd(&s_h[(k >> shift) & 255u], 1);
+        int32_t sc = score[s];
+        if (LRU_UPDATE) {
+            sc = touched[s] ? 0 : sc - 1;
+            score[s] = sc;
+            touched[s] = 0;
+        }
+        const uint32_t k = score_key(sc);
+        if (active && (k & mask) == prefix) atomicAdd(&s_h[(k >> shift) & 255u], 1);
     }
+    if (!active) return;
     __syncthreads();
     if (s_h[threadIdx.x]) atomicAdd(&ctl->hist[threadIdx.x], s_h[threadIdx.x]);
 }
 
-// pick the digit in which the remaining-th smallest key falls; clears the histogram
+// Then one workgroup picks the digit in which the remaining-th smallest key falls, and clears the histogram.
 __global__ void __launch_bounds__(256) k_select_digit(int shift, Ctl* ctl) {
-    __shared__ int32_t s_h[256];
-    s_h[threadIdx.x] = ctl->hist[threadIdx.x];
-    __syncthreads();
+    __shared__ int32_t s_w[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int32_t h = ctl->hist[threadIdx.x];
     ctl->hist[threadIdx.x] = 0;
-    if (threadIdx.x == 0 && ctl->m > 0) {
-        int32_t rem = ctl->remaining, cum = 0;
-        int d = 0;
-        for (; d < 255; ++d) {
-            if (cum + s_h[d] >= rem) break;
-            cum += s_h[d];
-        }
-        ctl->prefix |= (uint32_t)d << shift;
-        ctl->mask |= 255u << shift;
-        ctl->remaining = rem - cum;               // entries to take among keys equal to the threshold so far
+    if (ctl->m <= 0) return;
+    int32_t inc = wave_inclusive_scan(h, lane);
+    if (lane == 63) s_w[wave] = inc;
+    __syncthreads();
+    for (int w = 0; w < wave; ++w) inc += s_w[w];
+    const int32_t rem = ctl->remaining;
+    const uint32_t prefix = ctl->prefix, mask = ctl->mask;
+    // the first bin whose inclusive count reaches rem; bin 255 if none does
+    const bool mine = (inc >= rem && inc - h < rem) || (threadIdx.x == 255 && inc < rem);
+    __syncthreads();
+    if (mine) {
+        ctl->prefix = prefix | ((uint32_t)threadIdx.x << shift);
+        ctl->mask = mask | (255u << shift);
+        ctl->remaining = rem - (inc - h);           // entries to take among keys equal to the threshold so far
     }
 }
 
-// eq[s] = 1 where the key equals the threshold (to rank the ties by slot)
-__global__ void __launch_bounds__(256) k_flag_equal(const int32_t* __restrict__ score, int64_t capacity, const Ctl* ctl,
-                                                    int32_t* __restrict__ eq) {
-    const int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (s < capacity) eq[s] = (ctl->m > 0 && score_key(score[s]) == ctl->prefix) ? 1 : 0;
-}
-// take[s] = key below the threshold, or equal to it and among the first `remaining` of the ties
-__global__ void __launch_bounds__(256) k_flag_take(const int32_t* __restrict__ score, int64_t capacity, const Ctl* ctl,
-                                                   const int32_t* __restrict__ eq_rank, int32_t* __restrict__ take) {
-    const int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (s < capacity) {
-        int t = 0;
-        if (ctl->m > 0) {
-            const uint32_t k = score_key(score[s]);
-            t = k < ctl->prefix || (k == ctl->prefix && eq_rank[s] < ctl->remaining);
-        }
-        take[s] = t;
+// The victims in ascending slot order: every entry below the threshold key and the first `remaining`
+// entries equal to it.  Packed count: entries below in the high word, equal entries in the low word.
+struct Victims {
+    const int32_t* score;
+    const Ctl* ctl;
+    int32_t* victims;
+    __device__ int64_t count(int64_t s) const {
+        if (ctl->m <= 0) return 0;
+        const uint32_t k = score_key(score[s]), t = ctl->prefix;
+        return k < t ? (int64_t(1) << 32) : (k == t ? 1 : 0);
     }
-}
-// victims[pos] = slot, in ascending slot order (needs the flags again: recomputed)
-__global__ void __launch_bounds__(256) k_collect_victims(const int32_t* __restrict__ score, int64_t capacity, const Ctl* ctl,
-                                                         const int32_t* __restrict__ eq_rank, const int32_t* __restrict__ pos,
-                                                         int32_t* __restrict__ victims) {
-    const int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (s < capacity && ctl->m > 0) {
-        const uint32_t k = score_key(score[s]);
-        if (k < ctl->prefix || (k == ctl->prefix && eq_rank[s] < ctl->remaining)) victims[pos[s]] = (int32_t)s;
+    __device__ void emit(int64_t s, int64_t before) const {
+        const int64_t below_before = before >> 32, eq_before = before & 0xffffffffll, rem = ctl->remaining;
+        const bool below = score_key(score[s]) < ctl->prefix;
+        if (below || eq_before < rem) victims[below_before + (eq_before < rem ? eq_before : rem)] = (int32_t)s;
     }
-}
+    __device__ void total(int64_t) const {}
+};
+
 __global__ void __launch_bounds__(256) k_fifo_victims(int64_t capacity, int32_t max_replace, int64_t* ring, const Ctl* ctl,
                                                       int32_t* __restrict__ victims) {
     const int32_t i = blockIdx.x * 256 + threadIdx.x;
@@ -342,12 +356,13 @@ __global__ void __launch_bounds__(256) k_insert(CacheState c, int policy, int32_
 inline unsigned blocks_for(int64_t n, int per = 256) { return (unsigned)std::max<int64_t>(1, (n + per - 1) / per); }
 inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
-// exclusive scan of a[0..n) in place; total to *total; sums = scratch for ceil(n/1024) ints
-void scan_i32(int32_t* a, int64_t n, int32_t* sums, int32_t* total, hipStream_t stream) {
+// flagged elements of [0, n) through the functor (see above); sums = scratch for ceil(n/1024) + 1 int64
+template <class F>
+void compact_flagged(const F& f, int64_t n, int64_t* sums, hipStream_t stream) {
     const int64_t tiles = (n + kScanTile - 1) / kScanTile;
-    if (tiles > 0) hipLaunchKernelGGL(k_scan_tile_sums, dim3((unsigned)tiles), dim3(256), 0, stream, a, n, sums);
-    hipLaunchKernelGGL(k_scan_sums, dim3(1), dim3(1024), 0, stream, sums, tiles, total);
-    if (tiles > 0) hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)tiles), dim3(256), 0, stream, a, n, sums);
+    if (tiles > 0) hipLaunchKernelGGL((k_flag_tile_sums<F>), dim3((unsigned)tiles), dim3(256), 0, stream, f, n, sums);
+    hipLaunchKernelGGL((k_flag_scan_sums<F>), dim3(1), dim3(1024), 0, stream, f, sums, tiles);
+    if (tiles > 0) hipLaunchKernelGGL((k_flag_collect<F>), dim3((unsigned)tiles), dim3(256), 0, stream, f, n, sums);
 }
 
 }  // namespace
@@ -361,7 +376,8 @@ struct tns_cache {
 namespace {
 struct Workspace {
     Ctl* ctl;
-    int32_t *slots, *flag, *new_ids, *victims, *eq, *take, *sums, *dummy_total;
+    int32_t *slots, *new_ids, *victims;
+    int64_t* sums;
     size_t bytes;
 };
 Workspace carve(const tns_cache* c, int64_t B, void* base) {
@@ -372,13 +388,9 @@ Workspace carve(const tns_cache* c, int64_t B, void* base) {
     const int64_t cap = c->cfg.capacity;
     w.ctl = reinterpret_cast<Ctl*>(take(sizeof(Ctl)));
     w.slots = reinterpret_cast<int32_t*>(take((size_t)B * 4));
-    w.flag = reinterpret_cast<int32_t*>(take((size_t)B * 4));
     w.new_ids = reinterpret_cast<int32_t*>(take((size_t)std::max(c->max_replace, 1) * 4));
     w.victims = reinterpret_cast<int32_t*>(take((size_t)std::max(c->max_replace, 1) * 4));
-    w.eq = reinterpret_cast<int32_t*>(take((size_t)cap * 4));
-    w.take = reinterpret_cast<int32_t*>(take((size_t)cap * 4));
-    w.sums = reinterpret_cast<int32_t*>(take((size_t)(std::max(B, cap) / kScanTile + 2) * 4));
-    w.dummy_total = reinterpret_cast<int32_t*>(take(4));
+    w.sums = reinterpret_cast<int64_t*>(take((size_t)(std::max(B, cap) / kScanTile + 2) * 8));
     w.bytes = off;
     return w;
 }
@@ -467,29 +479,27 @@ int tns_cache_fetch(tns_cache* cache, int64_t B, const int32_t* d_ids, const flo
     else
         hipLaunchKernelGGL(k_gather<1>, dim3(blocks_for(B * dim)), dim3(256), 0, stream, st.rows, store, dim, B, d_ids, w.slots,
                            d_out);
-    if (policy == TNS_CACHE_LRU) hipLaunchKernelGGL(k_lru_scores, dim3(blocks_for(C)), dim3(256), 0, stream, st.score, st.touched, C);
+    const bool select = maxrep > 0 && policy != TNS_CACHE_FIFO;
+    // LRU: every score is decremented and the accessed entries are reset; done on the way by the first
+    // pass of the victim selection when there is one
+    if (policy == TNS_CACHE_LRU && !select)
+        hipLaunchKernelGGL(k_lru_scores, dim3(blocks_for(C)), dim3(256), 0, stream, st.score, st.touched, C);
     if (maxrep > 0) {
-        // distinct missed ids in order of first occurrence
-        hipLaunchKernelGGL(k_mark_first, dim3(blocks_for(B)), dim3(256), 0, stream, st.first_idx, B, d_ids, w.slots, w.flag);
-        scan_i32(w.flag, B, w.sums, &w.ctl->n_unique, stream);
-        hipLaunchKernelGGL(k_collect_new, dim3(blocks_for(B)), dim3(256), 0, stream, st.first_idx, B, d_ids, w.slots, w.flag,
-                           maxrep, w.new_ids, w.ctl);
-        // victims
+        compact_flagged(NewIds{st.first_idx, d_ids, w.slots, maxrep, w.new_ids, w.ctl}, B, w.sums, stream);
         if (policy == TNS_CACHE_FIFO) {
             hipLaunchKernelGGL(k_fifo_victims, dim3(blocks_for(maxrep)), dim3(256), 0, stream, C, maxrep, st.ring, w.ctl, w.victims);
             hipLaunchKernelGGL(k_fifo_advance, dim3(1), dim3(1), 0, stream, C, st.ring, w.ctl);
         } else {
-            const unsigned hb = (unsigned)std::min<int64_t>(blocks_for(C), 1024);
+            // few workgroups: their histograms are added to one global one with atomics
+            const unsigned hb = (unsigned)std::min<int64_t>(blocks_for(C), 256);
             for (int shift = 24; shift >= 0; shift -= 8) {
-                hipLaunchKernelGGL(k_select_hist, dim3(hb), dim3(256), 0, stream, st.score, C, shift, w.ctl);
+                if (shift == 24 && policy == TNS_CACHE_LRU)
+                    hipLaunchKernelGGL(k_select_hist<true>, dim3(hb), dim3(256), 0, stream, st.score, st.touched, C, shift, w.ctl);
+                else
+                    hipLaunchKernelGGL(k_select_hist<false>, dim3(hb), dim3(256), 0, stream, st.score, st.touched, C, shift, w.ctl);
                 hipLaunchKernelGGL(k_select_digit, dim3(1), dim3(256), 0, stream, shift, w.ctl);
             }
-            hipLaunchKernelGGL(k_flag_equal, dim3(blocks_for(C)), dim3(256), 0, stream, st.score, C, w.ctl, w.eq);
-            scan_i32(w.eq, C, w.sums, w.dummy_total, stream);
-            hipLaunchKernelGGL(k_flag_take, dim3(blocks_for(C)), dim3(256), 0, stream, st.score, C, w.ctl, w.eq, w.take);
-            scan_i32(w.take, C, w.sums, w.dummy_total, stream);
-            hipLaunchKernelGGL(k_collect_victims, dim3(blocks_for(C)), dim3(256), 0, stream, st.score, C, w.ctl, w.eq, w.take,
-                               w.victims);
+            compact_flagged(Victims{st.score, w.ctl, w.victims}, C, w.sums, stream);
         }
         hipLaunchKernelGGL(k_insert, dim3(blocks_for(maxrep, 4)), dim3(256), 0, stream, st, policy, dim, store, w.new_ids, w.victims,
                            w.ctl);

@@ -28,7 +28,7 @@ def wl_of(stream, name="tiny", fanout=10, tau=48):
 
 @pytest.mark.parametrize("policy", [0, 1])
 @pytest.mark.parametrize("inclusive", [0, 1])
-@pytest.mark.parametrize("f", [1, 2, 10, 25, 64])
+@pytest.mark.parametrize("f", [1, 2, 10, 13, 16, 25, 64])
 def test_tiny_streams_all_options(B, oracle_lib, policy, inclusive, f):
     st = W.tiny_stream(41, 3000, 23, 256, ties=True)
     wl = wl_of(st, fanout=f)

@@ -73,7 +73,11 @@ enum {
        tns_add_edges_device and are visible to the next tns_run on the same stream; there is no
        host copy, tns_add_edges is refused (TNS_ESTATE) and tns_commit has nothing to upload.
        Cannot be combined with the host placements or TNS_FLAG_NO_NODE_SLAB. */
-    TNS_FLAG_DEVICE_INGEST = 16
+    TNS_FLAG_DEVICE_INGEST = 16,
+    /* Keep edge positions as 64-bit values inside the kernels even while the edge array is small.  The
+       library switches to them by itself once the array passes 2^31 four-byte words (8 GiB); the
+       flag exists so that tests reach that code without such a store. */
+    TNS_FLAG_WIDE_POSITIONS = 32
 };
 
 typedef struct {

@@ -46,6 +46,21 @@ def test_tiny_streams_all_options(B, oracle_lib, policy, inclusive, f):
         plan.close()
 
 
+@pytest.mark.parametrize("policy", [0, 1])
+@pytest.mark.parametrize("f", [3, 10, 20])
+def test_64_bit_edge_positions(B, oracle_lib, policy, f):
+    # the kernels keep 64-bit positions once the edge array passes 8 GiB; forced here on a small store
+    st = W.tiny_stream(43, 5000, 31, 300, ties=True)
+    wl = wl_of(st, fanout=f, tau=16)
+    targets, t_start, t_end = W.random_queries(44, st, 2000 + 3)
+    plan = build_plan(B, wl, policy, 0, seed=8, flags=B.TNS_FLAG_WIDE_POSITIONS)
+    for tb in (t_start, None):
+        got = gpu_sample(plan, targets, tb, t_end)
+        ref = oracle_sample(oracle_lib, wl, targets, tb, t_end, None, f, policy, 0, 8)
+        assert_same(got, ref, oracle_lib, f"policy={policy} f={f}")
+    plan.close()
+
+
 def test_no_ties_long_lists_one_edge_per_batch(B, oracle_lib):
     st = W.tiny_stream(7, 700, 3, 1, ties=False)          # one edge per batch: longest possible lists
     wl = wl_of(st, fanout=10, tau=8)

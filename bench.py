@@ -210,7 +210,7 @@ def main() -> int:
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     ms_kernel = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
-    assert int(out["workspace"][4:8].view(torch.int32).item()) == 0, "chained scan timed out"
+    assert args.placement != "hbm" or int(out["workspace"][4:8].view(torch.int32).item()) == 0, "chained scan timed out"
 
     # for comparison, the same work as two steps: padded sampling, then stand-alone padding removal
     ev2 = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
@@ -260,7 +260,7 @@ def main() -> int:
                                f"policy={args.policy}, window={'0.25 span' if args.windowed else 'unbounded'}",
                    "queries": Q, "instances": wl.num_instances, "nodes_per_instance": wl.num_nodes,
                    "placement": args.placement, "ingest": args.ingest},
-        "roofline": {"bound": "hbm", "kernel": "tns_sample_kernel (padding removal fused)", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": "tns_sample_kernel (padding removal fused)" if args.placement == "hbm" else "tns_sample_kernel + tns_compact kernels", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "moved": moved, "copy_ceiling_GBs": copy_gbs,
                      "algorithmic_bytes_per_launch": alg_step, "bytes_breakdown": bytes_step,

@@ -198,7 +198,7 @@ TNS_API int tns_workspace(const tns_plan *plan, int64_t Q, size_t *bytes);
  * TNS_ESTATE before the first commit, TNS_ESIZE for a short workspace, TNS_EINVAL for
  * missing pointers, TNS_EHIP if a launch fails.
  *
- * With compaction both steps run in one kernel whose workgroups pass their dense
+ * With compaction (and the edge data in device memory) both steps run in one kernel whose workgroups pass their dense
  * offsets along a chain; a workgroup waits for its predecessors for a bounded time only.  Should
  * that bound ever be hit, the second 32-bit word of d_workspace is non-zero once the stream's
  * work is done and the dense outputs are invalid (the padded ones are not affected).

@@ -259,7 +259,7 @@ class Plan:
                  num_instances: int = 1, sizing: int = TNS_SIZING_ADAPTIVE, inclusive_end: int = 0, seed: int = 0,
                  device: int = 0, flags: int = 0):
         self.num_nodes, self.fanout, self.num_instances, self.device = num_nodes, fanout, num_instances, device
-        self.policy = policy
+        self.policy, self.flags = policy, flags
         self._h = tns_plan_create(num_nodes, fanout, policy, block_threshold, num_instances, sizing, inclusive_end,
                                   seed, device, flags)
 

@@ -540,8 +540,12 @@ int tns_run(tns_plan* plan, int64_t Q, const int32_t* d_targets, const float* d_
     a.out_eid = d_out_eid;
     a.out_ts = d_out_ts;
     a.out_count = d_out_count;
-    if (want_cmp) {
-        // one pass: sampling with the padding removal fused in
+    // One pass: sampling with the padding removal fused in.  With the edge data in host memory the reads
+    // cross the host link and what counts is how many of them are in flight: the plain sampling kernel
+    // keeps more waves resident than the fused one, so the two steps are run one after the other
+    // (C3, edge data on the host: 29.0 + 0.9 ms against 46.9 ms fused).
+    const bool fuse = want_cmp && !plan->d_edges.on_host;
+    if (fuse) {
         a.scan_ws = d_workspace;
         a.rowptr = d_rowptr;
         a.cmp_nbr = d_cmp_nbr;
@@ -550,6 +554,9 @@ int tns_run(tns_plan* plan, int64_t Q, const int32_t* d_targets, const float* d_
     }
     const hipError_t e = tns::launch_sample(a, stream);
     if (e != hipSuccess) return fail_hip(e, "launching the sampling kernel");
+    if (want_cmp && !fuse)
+        return run_compact(plan, Q, d_out_nbr, d_out_eid, d_out_ts, d_out_count, d_rowptr, d_cmp_nbr, d_cmp_eid,
+                           d_cmp_ts, d_workspace, stream);
     return TNS_OK;
 }
 

@@ -75,7 +75,7 @@ def cpu_baseline(wl, policy: int, seed: int, target_seconds: float, d_out, torch
     one_s = time.time() - t0
     adj.close()
     return {"value": done / spent, "unit": "elements/s", "cores": used, "kind": "oracle",
-            "sample": f"every {stride}th query of the batch from query 0 on, {done} queries, {spent:.1f} s "
+            "sample": f"the first {done} queries of the batch, in order, {spent:.1f} s "
                       f"(per-node list build {build_s:.1f} s not included)",
             "matches_gpu_on_sample": ok,
             "single_thread": {"value": n1 / one_s, "unit": "elements/s", "sample": f"the first {n1} queries, {one_s:.1f} s"}}

@@ -4,16 +4,21 @@
 // Thread mapping.  The paper runs one thread per sampled neighbour with the f threads of a
 // target adjacent.  On a 64-wide wavefront with dependent random reads (node entry -> block
 // record -> timestamps -> edge data) what limits throughput is the number of independent
-// chains in flight, so here the walk and the searches run one query per lane (64 independent
-// chains per wave), each lane leaves the edge positions it selected in LDS (the paper stages
-// candidate positions in shared memory for uniform sampling; here both policies do), and then
-// the whole wave gathers the edges and writes the padded rows cooperatively: lane l handles
-// flat slot it*64+l of the wave's 64*f slots, so every store instruction covers 256
-// consecutive bytes of each output array.
+// chains in flight and the number of different 128-byte lines a load instruction touches, so:
+//   * the walk runs one query per lane (64 independent chains per wave);
+//   * the node entries are fetched by the wave together, eight lanes per 128-byte line, and
+//     handed to their lanes through LDS;
+//   * each lane leaves the edge positions it selected in LDS (the paper stages candidate
+//     positions in shared memory for uniform sampling; here both policies do);
+//   * the in-block search of the window end (recent policy) and the gather of the selected edges
+//     are done by the whole wave, all loads of a phase issued before the first result is used:
+//     lane l handles flat slot it*64+l of the wave's 64*f slots, so every store instruction
+//     covers 256 consecutive bytes of each output array;
+//   * with the dense outputs requested, the workgroups pass their dense offsets along a chain
+//     (single-pass scan over tiles) and write the dense rows from registers.
 #include "tns_kernels.h"
 
 #include <algorithm>
-#include <cstdlib>
 #include <type_traits>
 
 namespace tns {

@@ -77,7 +77,11 @@ enum {
     /* Keep edge positions as 64-bit values inside the kernels even while the edge array is small.  The
        library switches to them by itself once the array passes 2^31 four-byte words (8 GiB); the
        flag exists so that tests reach that code without such a store. */
-    TNS_FLAG_WIDE_POSITIONS = 32
+    TNS_FLAG_WIDE_POSITIONS = 32,
+    /* Test of the fused kernel's bounded wait: the tile tickets start at 1, so the first tile's
+       predecessor never reports.  Every kernel still ends (after the bound, about two seconds); the
+       second 32-bit word of the workspace is then 1 and the outputs are not valid. */
+    TNS_FLAG_TEST_LOST_TILE = 64
 };
 
 typedef struct {

@@ -206,7 +206,7 @@ int tns_plan_create(const tns_config* cfg, tns_plan** out) {
     if (cfg->inclusive_end != 0 && cfg->inclusive_end != 1) return fail(TNS_EINVAL, "inclusive_end must be 0 or 1");
     if (cfg->device < 0) return fail(TNS_EINVAL, "negative device ordinal");
     constexpr int32_t kKnownFlags = TNS_FLAG_NO_XCD_REMAP | TNS_FLAG_NO_NODE_SLAB | TNS_FLAG_EDGES_ON_HOST |
-                                    TNS_FLAG_ALL_ON_HOST | TNS_FLAG_DEVICE_INGEST | TNS_FLAG_WIDE_POSITIONS;
+                                    TNS_FLAG_ALL_ON_HOST | TNS_FLAG_DEVICE_INGEST | TNS_FLAG_WIDE_POSITIONS | TNS_FLAG_TEST_LOST_TILE;
     if (cfg->flags & ~kKnownFlags) return fail(TNS_EINVAL, "unknown bit in flags");
     if ((cfg->flags & TNS_FLAG_EDGES_ON_HOST) && (cfg->flags & TNS_FLAG_ALL_ON_HOST))
         return fail(TNS_EINVAL, "TNS_FLAG_EDGES_ON_HOST and TNS_FLAG_ALL_ON_HOST exclude each other");
@@ -494,6 +494,7 @@ static int fill_sample_args(tns_plan* plan, int64_t Q, const int32_t* d_targets,
     a.policy = plan->cfg.policy;
     a.inclusive_end = plan->cfg.inclusive_end;
     a.xcd_remap = (plan->cfg.flags & TNS_FLAG_NO_XCD_REMAP) ? 0 : 1;
+    a.first_ticket = (plan->cfg.flags & TNS_FLAG_TEST_LOST_TILE) ? 1 : 0;
     a.wide_offsets = (plan->d_edges.used * 32 >= (int64_t(1) << 31) || (plan->cfg.flags & TNS_FLAG_WIDE_POSITIONS)) ? 1 : 0;   // word indices beyond int32
     return TNS_OK;
 }

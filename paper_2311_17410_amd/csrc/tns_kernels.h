@@ -49,6 +49,7 @@ struct SampleArgs {
     int32_t inclusive_end;
     int32_t xcd_remap;
     int32_t wide_offsets;  // edge array has 2^31 or more entries: 64-bit positions in LDS
+    int32_t first_ticket;  // 0; tests of the chained scan's bounded wait pass 1: tile 0 then never exists
 };
 
 struct CompactArgs {

@@ -117,10 +117,10 @@ __device__ __forceinline__ int64_t lookback_exclusive(ScanWorkspace* ws, int64_t
 // Clears the ticket, the error flag and the tile states before a fused launch (a kernel rather
 // than a memset, so that the launch sequence can be captured into a graph).
 __global__ void __launch_bounds__(256) tns_scan_init(ScanWorkspace* ws, int64_t num_tiles, int64_t* rowptr0, int64_t Q,
-                                                     const int64_t* Q_dev, int64_t* total_out) {
+                                                     const int64_t* Q_dev, int64_t* total_out, uint32_t first_ticket) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i == 0) {
-        ws->ticket = 0;
+        ws->ticket = first_ticket;
         ws->error = 0;
         if (Q_dev && *Q_dev < Q) Q = *Q_dev;
         if (Q <= 0) {          // no query will write the end of rowptr
@@ -857,9 +857,10 @@ hipError_t launch_sample_t(const SampleArgs& a, hipStream_t stream) {
     const int64_t grid = (a.Q + per_wg - 1) / per_wg;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     if (FUSED) {
-        const unsigned init_grid = (unsigned)std::max<int64_t>(1, (grid + 255) / 256);
+        // one state more than tiles: the workspace has it, and a test that starts the tickets at 1 uses it
+        const unsigned init_grid = (unsigned)std::max<int64_t>(1, (grid + 1 + 255) / 256);
         hipLaunchKernelGGL(tns_scan_init, dim3(init_grid), dim3(256), 0, stream, static_cast<ScanWorkspace*>(a.scan_ws),
-                           grid, a.rowptr, a.Q, a.Q_dev, a.total_out);
+                           grid + 1, a.rowptr, a.Q, a.Q_dev, a.total_out, (uint32_t)a.first_ticket);
     }
     if (grid <= 0) return hipGetLastError();
     const size_t lds = chunk * waves;

@@ -41,7 +41,7 @@ def test_argument_validation():
                        (dict(num_nodes=4, fanout=3, num_instances=0), B.TNS_EINVAL),
                        (dict(num_nodes=4, fanout=3, sizing=3), B.TNS_EINVAL),
                        (dict(num_nodes=4, fanout=3, inclusive_end=2), B.TNS_EINVAL),
-                       (dict(num_nodes=4, fanout=3, flags=64), B.TNS_EINVAL),
+                       (dict(num_nodes=4, fanout=3, flags=128), B.TNS_EINVAL),
                        (dict(num_nodes=4, fanout=3, flags=B.TNS_FLAG_DEVICE_INGEST | B.TNS_FLAG_EDGES_ON_HOST), B.TNS_EINVAL),
                        (dict(num_nodes=4, fanout=3, flags=B.TNS_FLAG_DEVICE_INGEST | B.TNS_FLAG_NO_NODE_SLAB), B.TNS_EINVAL),
                        (dict(num_nodes=4, fanout=3, flags=B.TNS_FLAG_EDGES_ON_HOST | B.TNS_FLAG_ALL_ON_HOST), B.TNS_EINVAL)]:

@@ -176,6 +176,25 @@ def test_standalone_compaction_equals_fused(B, oracle_lib):
     plan.close()
 
 
+def test_bounded_wait_of_the_chained_scan_ends(B):
+    # failure handling, forced from the host: the tile tickets start at 1, so tile 0 never exists and the
+    # first tile's look-back can only end by its bound; every kernel must still finish, and the error
+    # word of the workspace must say what happened
+    import time
+    import torch
+    st = W.tiny_stream(17, 40000, 500, 4096, ties=False)
+    wl = wl_of(st, fanout=10)
+    plan = build_plan(B, wl, 0, flags=B.TNS_FLAG_TEST_LOST_TILE)
+    dev = torch.device("cuda", 0)
+    d_t, d_e = torch.from_numpy(st.src).to(dev), torch.from_numpy(st.ts).to(dev)
+    t0 = time.time()
+    out = plan.run(d_t, None, d_e)
+    torch.cuda.synchronize()
+    assert time.time() - t0 < 60
+    assert int(out["workspace"][4:8].view(torch.int32).item()) == 1
+    plan.close()
+
+
 def test_step_replayed_from_a_hip_graph(B, oracle_lib):
     # tns_run only enqueues kernels (the chained scan's state is cleared by a kernel, not by a memset),
     # so a step can be captured once and replayed; every replay is checked, with eager work in between

@@ -132,7 +132,7 @@ int grow_device(DeviceArray<T>& d, int64_t need, hipStream_t stream, const char*
         e = hipMemcpyAsync(p, d.ptr, (size_t)d.used * sizeof(T), hipMemcpyDeviceToDevice, stream);
         if (e == hipSuccess) e = hipStreamSynchronize(stream);
         if (e != hipSuccess) {
-            (void)hipFree(p);
+            (void)(d.on_host ? hipHostFree(p) : hipFree(p));
             return fail_hip(e, what);
         }
     }

@@ -91,3 +91,24 @@ def test_paper_scale_shapes_and_restore(KB):
     r_out, r_hit = ref.fetch(ids, store)
     assert np.array_equal(out.cpu().numpy(), r_out) and np.array_equal(hit.cpu().numpy().astype(bool), r_hit)
     gpu.close()
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_configuration(KB, seed):
+    # seeded differential test over capacities, row widths, replacement caps, batch sizes and id distributions
+    rng = np.random.default_rng(500 + seed)
+    n = int(rng.choice([1, 5, 60, 1000, 20_000]))
+    cap = int(rng.integers(1, max(2, min(n, 3000) + 1)))
+    dim = int(rng.choice([1, 3, 4, 8, 33, 172]))
+    lam = float(rng.choice([0.01, 0.2, 0.5, 1.0]))
+    policy = int(rng.integers(0, 3))
+    batches = []
+    for _ in range(int(rng.integers(3, 25))):
+        b = int(rng.integers(1, 3000))
+        ids = (rng.zipf(1.15, b) % n) if rng.integers(0, 2) else rng.integers(0, n, b)
+        if rng.integers(0, 5) == 0:
+            ids = ids.astype(np.int64)
+            ids[rng.integers(0, b)] = n + int(rng.integers(0, 10))      # an id outside the range
+        batches.append(ids)
+    gpu, *_ = run_sequence(KB, policy, n, cap, dim, lam, batches, seed)
+    gpu.close()

@@ -371,6 +371,10 @@ struct tns_cache {
     tns_cache_config cfg;
     CacheState st{};
     int32_t max_replace = 0;
+    // the update (scores, victims) runs beside the row gather on a stream of the cache's own,
+    // forked from and joined back into the caller's stream with these events
+    hipStream_t side = nullptr;
+    hipEvent_t forked = nullptr, joined = nullptr;
 };
 
 namespace {
@@ -426,6 +430,13 @@ int tns_cache_create(const tns_cache_config* cfg, tns_cache** out) {
             return fail_hip(e, "allocating the cache");
         }
     }
+    hipError_t es = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
+    if (es == hipSuccess) es = hipEventCreateWithFlags(&c->forked, hipEventDisableTiming);
+    if (es == hipSuccess) es = hipEventCreateWithFlags(&c->joined, hipEventDisableTiming);
+    if (es != hipSuccess) {
+        tns_cache_destroy(c);
+        return fail_hip(es, "creating the cache's stream and events");
+    }
     hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(N)), dim3(256), 0, nullptr, c->st.slot_of, N, -1);
     hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(N)), dim3(256), 0, nullptr, c->st.first_idx, N, kNoIndex);
     hipLaunchKernelGGL(k_fill_i32, dim3(blocks_for(C)), dim3(256), 0, nullptr, c->st.id_of, C, -1);
@@ -472,6 +483,40 @@ int tns_cache_fetch(tns_cache* cache, int64_t B, const int32_t* d_ids, const flo
     const int32_t maxrep = cache->max_replace;
 
     hipLaunchKernelGGL(k_lookup, dim3(blocks_for(B)), dim3(256), 0, stream, st, policy, N, B, d_ids, w.slots, d_hit, w.ctl);
+    // From here the update (scores, distinct misses, victims: many short kernels over the score vector) runs on
+    // the cache's own stream beside the row gather, which is bound by memory bandwidth; both only read what the
+    // lookup wrote.  The insertion changes rows and maps and waits for both.
+    const bool select = maxrep > 0 && policy != TNS_CACHE_FIFO;
+    const bool update = maxrep > 0 || policy == TNS_CACHE_LRU;
+    hipStream_t us = stream;
+    if (update) {
+        hipError_t ef = hipEventRecord(cache->forked, stream);
+        if (ef == hipSuccess) ef = hipStreamWaitEvent(cache->side, cache->forked, 0);
+        if (ef != hipSuccess) return fail_hip(ef, "forking the cache update");
+        us = cache->side;
+    }
+    // LRU: every score is decremented and the accessed entries are reset; done on the way by the first
+    // pass of the victim selection when there is one
+    if (policy == TNS_CACHE_LRU && !select)
+        hipLaunchKernelGGL(k_lru_scores, dim3(blocks_for(C)), dim3(256), 0, us, st.score, st.touched, C);
+    if (maxrep > 0) {
+        compact_flagged(NewIds{st.first_idx, d_ids, w.slots, maxrep, w.new_ids, w.ctl}, B, w.sums, us);
+        if (policy == TNS_CACHE_FIFO) {
+            hipLaunchKernelGGL(k_fifo_victims, dim3(blocks_for(maxrep)), dim3(256), 0, us, C, maxrep, st.ring, w.ctl, w.victims);
+            hipLaunchKernelGGL(k_fifo_advance, dim3(1), dim3(1), 0, us, C, st.ring, w.ctl);
+        } else {
+            // few workgroups: their histograms are added to one global one with atomics
+            const unsigned hb = (unsigned)std::min<int64_t>(blocks_for(C), 256);
+            for (int shift = 24; shift >= 0; shift -= 8) {
+                if (shift == 24 && policy == TNS_CACHE_LRU)
+                    hipLaunchKernelGGL(k_select_hist<true>, dim3(hb), dim3(256), 0, us, st.score, st.touched, C, shift, w.ctl);
+                else
+                    hipLaunchKernelGGL(k_select_hist<false>, dim3(hb), dim3(256), 0, us, st.score, st.touched, C, shift, w.ctl);
+                hipLaunchKernelGGL(k_select_digit, dim3(1), dim3(256), 0, us, shift, w.ctl);
+            }
+            compact_flagged(Victims{st.score, w.ctl, w.victims}, C, w.sums, us);
+        }
+    }
     const bool vec4 = dim % 4 == 0 && ((reinterpret_cast<uintptr_t>(store) | reinterpret_cast<uintptr_t>(d_out)) & 15) == 0;
     if (vec4)
         hipLaunchKernelGGL(k_gather<4>, dim3(blocks_for(B * (dim / 4))), dim3(256), 0, stream, st.rows, store, dim, B, d_ids,
@@ -479,31 +524,14 @@ int tns_cache_fetch(tns_cache* cache, int64_t B, const int32_t* d_ids, const flo
     else
         hipLaunchKernelGGL(k_gather<1>, dim3(blocks_for(B * dim)), dim3(256), 0, stream, st.rows, store, dim, B, d_ids, w.slots,
                            d_out);
-    const bool select = maxrep > 0 && policy != TNS_CACHE_FIFO;
-    // LRU: every score is decremented and the accessed entries are reset; done on the way by the first
-    // pass of the victim selection when there is one
-    if (policy == TNS_CACHE_LRU && !select)
-        hipLaunchKernelGGL(k_lru_scores, dim3(blocks_for(C)), dim3(256), 0, stream, st.score, st.touched, C);
-    if (maxrep > 0) {
-        compact_flagged(NewIds{st.first_idx, d_ids, w.slots, maxrep, w.new_ids, w.ctl}, B, w.sums, stream);
-        if (policy == TNS_CACHE_FIFO) {
-            hipLaunchKernelGGL(k_fifo_victims, dim3(blocks_for(maxrep)), dim3(256), 0, stream, C, maxrep, st.ring, w.ctl, w.victims);
-            hipLaunchKernelGGL(k_fifo_advance, dim3(1), dim3(1), 0, stream, C, st.ring, w.ctl);
-        } else {
-            // few workgroups: their histograms are added to one global one with atomics
-            const unsigned hb = (unsigned)std::min<int64_t>(blocks_for(C), 256);
-            for (int shift = 24; shift >= 0; shift -= 8) {
-                if (shift == 24 && policy == TNS_CACHE_LRU)
-                    hipLaunchKernelGGL(k_select_hist<true>, dim3(hb), dim3(256), 0, stream, st.score, st.touched, C, shift, w.ctl);
-                else
-                    hipLaunchKernelGGL(k_select_hist<false>, dim3(hb), dim3(256), 0, stream, st.score, st.touched, C, shift, w.ctl);
-                hipLaunchKernelGGL(k_select_digit, dim3(1), dim3(256), 0, stream, shift, w.ctl);
-            }
-            compact_flagged(Victims{st.score, w.ctl, w.victims}, C, w.sums, stream);
-        }
+    if (update) {
+        hipError_t ej = hipEventRecord(cache->joined, cache->side);
+        if (ej == hipSuccess) ej = hipStreamWaitEvent(stream, cache->joined, 0);
+        if (ej != hipSuccess) return fail_hip(ej, "joining the cache update");
+    }
+    if (maxrep > 0)
         hipLaunchKernelGGL(k_insert, dim3(blocks_for(maxrep, 4)), dim3(256), 0, stream, st, policy, dim, store, w.new_ids, w.victims,
                            w.ctl);
-    }
     hipLaunchKernelGGL(k_clear_first, dim3(blocks_for(B)), dim3(256), 0, stream, st.first_idx, B, d_ids, w.slots);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail_hip(e, "launching the cache kernels");
@@ -576,6 +604,9 @@ int tns_cache_destroy(tns_cache* cache) {
                         cache->st.touched, cache->st.rows,      cache->st.counters, cache->st.ring};
         for (void* p : ptrs)
             if (p) (void)hipFree(p);
+        if (cache->forked) (void)hipEventDestroy(cache->forked);
+        if (cache->joined) (void)hipEventDestroy(cache->joined);
+        if (cache->side) (void)hipStreamDestroy(cache->side);
     }
     delete cache;
     return TNS_OK;

@@ -58,7 +58,9 @@ TNS_API int tns_cache_workspace(const tns_cache *cache, int64_t B, size_t *bytes
  *   d_out[B*dim]  DEVICE; row b receives the features of d_ids[b]
  *   d_hit[B]      DEVICE, may be NULL; 1 if the row came from the cache
  *   d_workspace   at least tns_cache_workspace() bytes, 256-byte aligned
- * Only enqueues kernels on hip_stream; never allocates or blocks.
+ * Only enqueues work; never allocates or blocks.  Part of the update runs on a stream the cache owns,
+ * forked from hip_stream after the lookup and joined back before the insertion (event record / wait), so
+ * to the caller everything is ordered on hip_stream, also when hip_stream is being captured into a graph.
  */
 TNS_API int tns_cache_fetch(tns_cache *cache, int64_t B, const int32_t *d_ids, const float *store, float *d_out,
                             uint8_t *d_hit, void *d_workspace, size_t workspace_bytes, void *hip_stream);

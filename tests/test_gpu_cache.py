@@ -112,3 +112,40 @@ def test_random_configuration(KB, seed):
         batches.append(ids)
     gpu, *_ = run_sequence(KB, policy, n, cap, dim, lam, batches, seed)
     gpu.close()
+
+
+def test_fetch_replayed_from_a_hip_graph(KB):
+    # the fetch forks part of its work onto a stream of the cache's own and joins it again; captured once and
+    # replayed, every replay must behave like one more fetch of the same batch (state and rows checked each time)
+    import torch
+    dev = torch.device("cuda", 0)
+    rng = np.random.default_rng(77)
+    n, cap, dim = 5000, 400, 20
+    store = rng.standard_normal((n, dim)).astype(np.float32)
+    d_store = torch.from_numpy(store).to(dev)
+    ids = (rng.zipf(1.1, 3000) % n).astype(np.int32)
+    d_ids = torch.from_numpy(ids).to(dev)
+    for policy in (CO.LRU, CO.LFU, CO.FIFO):
+        ref = CO.VectorCache(n, cap, dim, policy, 0.2)
+        gpu = KB.Cache(n, cap, dim, policy, 0.2)
+        out = torch.empty((len(ids), dim), dtype=torch.float32, device=dev)
+        hit = torch.empty(len(ids), dtype=torch.uint8, device=dev)
+        gpu.fetch(d_ids, d_store, out, hit)                     # eager once (also allocates the workspace)
+        ref.fetch(ids, store)
+        torch.cuda.synchronize()
+        graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+        with torch.cuda.graph(graph, stream=side):
+            gpu.fetch(d_ids, d_store, out, hit)
+        for rep in range(3):
+            out.zero_()
+            assert float(d_store.sum().item()) == float(d_store.sum().item())     # unrelated eager work and a sync
+            graph.replay()
+            torch.cuda.synchronize()
+            r_out, r_hit = ref.fetch(ids, store)
+            assert np.array_equal(out.cpu().numpy(), r_out) and np.array_equal(hit.cpu().numpy().astype(bool), r_hit), (policy, rep)
+            st = gpu.save()
+            assert np.array_equal(st["id_of"], ref.id_of), (policy, rep)
+            if policy != CO.FIFO:
+                assert np.array_equal(st["score"], ref.score), (policy, rep)
+        del graph
+        gpu.close()

@@ -587,8 +587,9 @@ int tns_workspace_khop(const tns_plan* plan, int32_t num_hops, const int32_t* fa
     if (num_hops < 1 || num_hops > kMaxHops) return fail(TNS_EINVAL, "num_hops must be in [1, 8]");
     int64_t caps[kMaxHops];
     if (!khop_caps(num_hops, fanouts, Q, caps)) return fail(TNS_ESIZE, "fan-out out of range or more than 2^36 queries in a hop");
+    // one chained-scan region per hop, so that a single launch can clear them all before the first hop
     size_t scan = 0;
-    for (int h = 0; h < num_hops; ++h) scan = std::max(scan, tns::compact_workspace_bytes(caps[h]));
+    for (int h = 0; h < num_hops; ++h) scan += tns::compact_workspace_bytes(caps[h]);
     *bytes = khop_header_bytes(num_hops, plan->cfg.num_instances) + scan;
     return TNS_OK;
 }
@@ -622,7 +623,13 @@ int tns_run_khop(tns_plan* plan, int32_t num_hops, const int32_t* fanouts, float
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int32_t I = plan->cfg.num_instances;
     int64_t* header = static_cast<int64_t*>(d_workspace);
-    void* scan_ws = static_cast<unsigned char*>(d_workspace) + khop_header_bytes(num_hops, I);
+    unsigned char* scan_ws = static_cast<unsigned char*>(d_workspace) + khop_header_bytes(num_hops, I);
+    {
+        size_t scan = 0;
+        for (int h = 0; h < num_hops; ++h) scan += tns::compact_workspace_bytes(caps[h]);
+        const hipError_t e = tns::launch_scan_clear(scan_ws, scan, stream);
+        if (e != hipSuccess) return fail_hip(e, "clearing the chained-scan workspace");
+    }
 
     for (int h = 0; h < num_hops; ++h) {
         const tns_hop_buffers& b = hops[h];
@@ -636,6 +643,8 @@ int tns_run_khop(tns_plan* plan, int32_t num_hops, const int32_t* fanouts, float
         a.out_count = b.count;
         a.total_out = total;
         a.scan_ws = scan_ws;                                    // sampling with the padding removal fused in
+        a.scan_ready = Q > 0 ? 1 : 0;                           // cleared above, together with the other hops' regions
+        scan_ws += tns::compact_workspace_bytes(caps[h]);
         a.rowptr = b.rowptr;
         a.cmp_nbr = b.cmp_nbr;
         a.cmp_eid = b.cmp_eid;

@@ -50,6 +50,7 @@ struct SampleArgs {
     int32_t xcd_remap;
     int32_t wide_offsets;  // edge array has 2^31 or more entries: 64-bit positions in LDS
     int32_t first_ticket;  // 0; tests of the chained scan's bounded wait pass 1: tile 0 then never exists
+    int32_t scan_ready;    // scan_ws is already cleared (multi-hop: one clearing launch for all hops)
 };
 
 struct CompactArgs {
@@ -75,6 +76,8 @@ size_t compact_workspace_bytes(int64_t Q);
 // Both only enqueue kernels on `stream`; they return the first launch error.
 hipError_t launch_sample(const SampleArgs& a, hipStream_t stream);
 hipError_t launch_compact(const CompactArgs& a, hipStream_t stream);
+// Clears `bytes` (a multiple of 8) of chained-scan workspace with a kernel (capturable, unlike a memset).
+hipError_t launch_scan_clear(void* ws, size_t bytes, hipStream_t stream);
 hipError_t launch_hop_inst_rowptr(const int64_t* cur, const int64_t* rowptr, int32_t num_instances, int64_t* next,
                                   hipStream_t stream);
 

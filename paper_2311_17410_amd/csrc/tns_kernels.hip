@@ -131,6 +131,11 @@ __global__ void __launch_bounds__(256) tns_scan_init(ScanWorkspace* ws, int64_t 
     if (i < num_tiles) ws->status[i] = 0;
 }
 
+__global__ void __launch_bounds__(256) tns_scan_clear(uint64_t* ws, int64_t words) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < words) ws[i] = 0;
+}
+
 // Unsigned index type of the same width as the LDS position entries: with a 32-bit index the edge
 // load is addressed as base + 32-bit offset, one register per address.
 template <typename pos_t> struct index_of { using type = uint64_t; };
@@ -402,6 +407,10 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256, FUSED ? 4 : 6) tns_sample_
     const int32_t f = p.fanout;
     // number of queries: the host's bound, or fewer when the count lives on the device (later hops)
     const int64_t Q = p.Q_dev ? min(p.Q, *p.Q_dev) : p.Q;
+    if (FUSED && Q <= 0 && tile == 0 && threadIdx.x == 0) {      // no query will write the end of rowptr
+        p.rowptr[0] = 0;
+        if (p.total_out) *p.total_out = 0;
+    }
 
     Walk<POLICY, INCL, pos_t> w;
     w.f = f;
@@ -856,7 +865,7 @@ hipError_t launch_sample_t(const SampleArgs& a, hipStream_t stream) {
     const int64_t per_wg = (int64_t)waves * kWave;
     const int64_t grid = (a.Q + per_wg - 1) / per_wg;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
-    if (FUSED) {
+    if (FUSED && !a.scan_ready) {
         // one state more than tiles: the workspace has it, and a test that starts the tickets at 1 uses it
         const unsigned init_grid = (unsigned)std::max<int64_t>(1, (grid + 1 + 255) / 256);
         hipLaunchKernelGGL(tns_scan_init, dim3(init_grid), dim3(256), 0, stream, static_cast<ScanWorkspace*>(a.scan_ws),
@@ -893,6 +902,13 @@ hipError_t launch_sample(const SampleArgs& a, hipStream_t stream) {
     if (a.scan_ws) return a.policy == 0 ? TNS_DISPATCH(0, false, true) : TNS_DISPATCH(1, false, true);
     return a.policy == 0 ? TNS_DISPATCH(0, false, false) : TNS_DISPATCH(1, false, false);
 #undef TNS_DISPATCH
+}
+
+hipError_t launch_scan_clear(void* ws, size_t bytes, hipStream_t stream) {
+    const int64_t words = (int64_t)(bytes / 8);
+    if (words > 0)
+        hipLaunchKernelGGL(tns_scan_clear, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, stream, static_cast<uint64_t*>(ws), words);
+    return hipGetLastError();
 }
 
 hipError_t launch_hop_inst_rowptr(const int64_t* cur, const int64_t* rowptr, int32_t num_instances, int64_t* next,

@@ -654,7 +654,7 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256, FUSED ? 4 : 6) tns_sample_
         };
         auto write_rowptr = [&](int64_t row) {
             if (q < Q) {
-                p.rowptr[q] = row;
+                __builtin_nontemporal_store(row, &p.rowptr[q]);
                 if (q == Q - 1) {
                     p.rowptr[Q] = row + k;
                     if (p.total_out) *p.total_out = row + k;

@@ -106,16 +106,13 @@ def main() -> int:
     cpu = None
     if args.cpu_seconds > 0:
         import oracle
+        from oracle import khop_oracle
         adj = oracle.Adjacency(st.num_nodes, st.src, st.dst, st.ts)
         k = min(Q, 1 << 22)
         t0 = time.perf_counter()
-        tg, te, done, ok = h_src[:k], h_ts[:k], 0, True
-        for h, f in zip(hops, fanouts):
-            ref = adj.sample(tg, None, te, f, policy=0, threads=16)
-            rowptr, cn, ce, ct = oracle.compact(ref)
-            done += len(tg)
-            ok = ok and bool(np.array_equal(h["cmp_eid"][:len(ce)].cpu().numpy(), ce))
-            tg, te = cn, ct
+        ref = khop_oracle.khop([adj], h_src[:k], None, h_ts[:k], None, fanouts, policy=0, threads=16)
+        done = sum(r["num_queries"] for r in ref)
+        ok = all(bool(np.array_equal(h["cmp_eid"][:len(r["cmp_eid"])].cpu().numpy(), r["cmp_eid"])) for h, r in zip(hops, ref))
         cpu_s = time.perf_counter() - t0
         cpu = {"value": done / cpu_s, "unit": "elements/s", "cores": 16, "kind": "oracle",
                "sample": f"the first {k} first-hop queries and everything they expand to ({done} queries), {cpu_s:.1f} s "

@@ -6,6 +6,8 @@ imports it.  Argument marshalling only; all arithmetic is in the two C files:
 
 * ``tns_oracle.c``        layout-free definition of the sampling result (O1-O5)
 * ``blockstore_oracle.c`` the paper's block store + Algorithm 1, step by step
+
+``khop_oracle.py`` chains the one-hop oracle into the multi-hop sampling of section 4.2.
 """
 from __future__ import annotations
 

@@ -77,11 +77,7 @@ enum {
     /* Keep edge positions as 64-bit values inside the kernels even while the edge array is small.  The
        library switches to them by itself once the array passes 2^31 four-byte words (8 GiB); the
        flag exists so that tests reach that code without such a store. */
-    TNS_FLAG_WIDE_POSITIONS = 32,
-    /* Test of the fused kernel's bounded wait: the tile tickets start at 1, so the first tile's
-       predecessor never reports.  Every kernel still ends (after the bound, about two seconds); the
-       second 32-bit word of the workspace is then 1 and the outputs are not valid. */
-    TNS_FLAG_TEST_LOST_TILE = 64
+    TNS_FLAG_WIDE_POSITIONS = 32
 };
 
 typedef struct {
@@ -163,6 +159,8 @@ TNS_API int tns_delete_edges(tns_plan *plan, int32_t instance, const int32_t *sr
 TNS_API int tns_delete_nodes(tns_plan *plan, int32_t instance, const int32_t *nodes, int64_t m, int32_t deleted);
 
 /*
+ * Section 3 (system overview): the store is not changed while a training round samples from it;
+ * new data is buffered and becomes visible at a defined point.  tns_commit is that point.
  * Make everything ingested so far visible to tns_run: uploads the changed parts of the
  * node table, block records and edge data to the device (allocating or growing device
  * memory as needed) on `hip_stream` (a hipStream_t, NULL = default stream) and waits for
@@ -171,7 +169,8 @@ TNS_API int tns_delete_nodes(tns_plan *plan, int32_t instance, const int32_t *no
  */
 TNS_API int tns_commit(tns_plan *plan, void *hip_stream);
 
-/* Bytes of DEVICE workspace tns_run needs for Q queries when compaction is requested (0 otherwise). */
+/* Bytes of DEVICE workspace tns_run needs for Q queries when the padding removal of section 5 is requested
+   (scan state of that step; the first 256 bytes hold the step's status word, see tns_run_status). */
 TNS_API int tns_workspace(const tns_plan *plan, int64_t Q, size_t *bytes);
 
 /*
@@ -203,15 +202,23 @@ TNS_API int tns_workspace(const tns_plan *plan, int64_t Q, size_t *bytes);
  * missing pointers, TNS_EHIP if a launch fails.
  *
  * With compaction (and the edge data in device memory) both steps run in one kernel whose workgroups pass their dense
- * offsets along a chain; a workgroup waits for its predecessors for a bounded time only.  Should
- * that bound ever be hit, the second 32-bit word of d_workspace is non-zero once the stream's
- * work is done and the dense outputs are invalid (the padded ones are not affected).
+ * offsets along a chain; a workgroup waits for its predecessors for a bounded time only (about two
+ * seconds).  Should that bound ever be hit, tns_run_status reports it once the stream's work is done:
+ * the dense outputs are then invalid and d_rowptr[Q] reads 0 (the padded outputs are not affected).
  */
 TNS_API int tns_run(tns_plan *plan, int64_t Q, const int32_t *d_targets, const float *d_t_start,
             const float *d_t_end, const int64_t *d_inst_rowptr, int64_t query_id_base,
             int32_t *d_out_nbr, int32_t *d_out_eid, float *d_out_ts, int32_t *d_out_count,
             int64_t *d_rowptr, int32_t *d_cmp_nbr, int32_t *d_cmp_eid, float *d_cmp_ts,
             void *d_workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Whether a bounded wait of the padding removal ran out in the last tns_run, tns_compact, tns_run_khop
+ * (any hop; the following hops then had no queries) that used `d_workspace` (DEVICE).  Waits for `hip_stream`, copies one
+ * word to the host; *timed_out (HOST) receives 0 or 1.  Not a step of the paper's method: the error
+ * report of this implementation's single-pass scan.
+ */
+TNS_API int tns_run_status(tns_plan *plan, const void *d_workspace, void *hip_stream, int32_t *timed_out);
 
 /*
  * Multi-hop sampling (section 4.2: the process is repeated per layer, the nodes sampled in one
@@ -297,7 +304,19 @@ TNS_API int tns_stats(const tns_plan *plan, int32_t instance, tns_stats_t *out);
 TNS_API int64_t tns_node_blocks(const tns_plan *plan, int32_t instance, int32_t node, int64_t max_blocks,
                         int32_t *cap, int32_t *size, float *t_min, float *t_max);
 
-/* Release the plan, its host store and its device memory.  NULL is allowed. */
+/*
+ * Measurement aid, not a step of the paper's method: a streaming kernel of exactly known traffic on
+ * `hip_stream`.  mode 0 copies `bytes` from d_src to d_dst (reads bytes, writes bytes), 1 only reads
+ * d_src (d_dst may be NULL), 2 only writes d_dst (d_src may be NULL); nontemporal != 0 puts the
+ * non-temporal hint on the loads and stores, as the sampling kernel does for data it touches once.
+ * DEVICE buffers, 16-byte aligned, bytes a multiple of 16.  The bench reports the rates as the box's
+ * practical ceiling and counter runs use the launches to calibrate the byte counters.
+ */
+TNS_API int tns_hbm_probe(int32_t mode, int32_t nontemporal, void *d_dst, const void *d_src, size_t bytes,
+                          void *hip_stream);
+
+/* Release the plan (the dynamic graph object of section 5's interface), its host store and its device
+   memory.  NULL is allowed. */
 TNS_API int tns_destroy(tns_plan *plan);
 
 /* Static description of a status code. */

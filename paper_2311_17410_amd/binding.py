@@ -25,10 +25,10 @@ TNS_FLAG_EDGES_ON_HOST = 4
 TNS_FLAG_ALL_ON_HOST = 8
 TNS_FLAG_DEVICE_INGEST = 16
 TNS_FLAG_WIDE_POSITIONS = 32
-TNS_FLAG_TEST_LOST_TILE = 64
+TNS_TEST_FLAG_LOST_TILE = 64      # csrc/tns_test_hooks.h: for the library's own tests, not in the public header
 
-EXPORTS = ["tns_plan_create", "tns_set_sampler", "tns_add_edges", "tns_add_edges_device", "tns_delete_edges", "tns_delete_nodes", "tns_commit", "tns_workspace", "tns_run", "tns_workspace_khop", "tns_run_khop", "tns_compact", "tns_traffic_model", "tns_stats",
-           "tns_node_blocks", "tns_destroy", "tns_strerror", "tns_last_error"]
+EXPORTS = ["tns_plan_create", "tns_set_sampler", "tns_add_edges", "tns_add_edges_device", "tns_delete_edges", "tns_delete_nodes", "tns_commit", "tns_workspace", "tns_run", "tns_run_status", "tns_workspace_khop", "tns_run_khop", "tns_compact", "tns_traffic_model", "tns_stats",
+           "tns_node_blocks", "tns_hbm_probe", "tns_destroy", "tns_strerror", "tns_last_error"]
 
 
 class tns_config(C.Structure):
@@ -65,6 +65,13 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
                                "(there is no fallback path)")
+        # One HIP runtime per process: PyTorch ships its own copy, and whichever copy is loaded first is the
+        # one both sides must use.  Loading torch first keeps the library on the runtime that owns the
+        # tensors and streams it is handed (without torch the library uses the system's runtime).
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = C.CDLL(LIB_PATH)
         vp, i32p, i64p, f32p = C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int64), C.POINTER(C.c_float)
         L.tns_plan_create.argtypes = [C.POINTER(tns_config), C.POINTER(vp)]
@@ -86,6 +93,8 @@ def lib():
         L.tns_run.argtypes = [vp, C.c_int64, vp, vp, vp, vp, C.c_int64, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                               C.c_size_t, vp]
         L.tns_run.restype = C.c_int
+        L.tns_run_status.argtypes = [vp, vp, vp, C.POINTER(C.c_int32)]
+        L.tns_run_status.restype = C.c_int
         L.tns_workspace_khop.argtypes = [vp, C.c_int32, i32p, C.c_int64, C.POINTER(C.c_size_t)]
         L.tns_workspace_khop.restype = C.c_int
         L.tns_run_khop.argtypes = [vp, C.c_int32, i32p, C.c_float, C.c_int64, vp, vp, vp, vp, C.c_int64,
@@ -99,6 +108,8 @@ def lib():
         L.tns_stats.restype = C.c_int
         L.tns_node_blocks.argtypes = [vp, C.c_int32, C.c_int32, C.c_int64, i32p, i32p, f32p, f32p]
         L.tns_node_blocks.restype = C.c_int64
+        L.tns_hbm_probe.argtypes = [C.c_int32, C.c_int32, vp, vp, C.c_size_t, vp]
+        L.tns_hbm_probe.restype = C.c_int
         L.tns_destroy.argtypes = [vp]
         L.tns_destroy.restype = C.c_int
         L.tns_strerror.argtypes = [C.c_int]
@@ -189,6 +200,15 @@ def tns_run(plan, Q: int, d_targets: int, d_t_start: int, d_t_end: int, d_inst_r
                          vp(d_cmp_eid), vp(d_cmp_ts), vp(d_workspace), workspace_bytes, vp(hip_stream)), "tns_run")
 
 
+def tns_run_status(plan, d_workspace: int = 0, hip_stream: int = 0) -> bool:
+    """True if a bounded wait of the padding removal ran out in the last step that used the workspace
+    (0 = the static scratch of tns_run_static).  Waits for the stream."""
+    out = C.c_int32()
+    _check(lib().tns_run_status(plan, C.c_void_p(d_workspace or None), C.c_void_p(hip_stream or None), C.byref(out)),
+           "tns_run_status")
+    return bool(out.value)
+
+
 def tns_workspace_khop(plan, fanouts, Q: int) -> int:
     fo = (C.c_int32 * len(fanouts))(*fanouts)
     n = C.c_size_t()
@@ -244,6 +264,12 @@ def tns_node_blocks(plan, instance: int, node: int) -> dict:
     lib().tns_node_blocks(plan, instance, node, n, cap.ctypes.data_as(i32p), size.ctypes.data_as(i32p),
                           tmin.ctypes.data_as(f32p), tmax.ctypes.data_as(f32p))
     return dict(cap=cap, size=size, t_min=tmin, t_max=tmax)
+
+
+def tns_hbm_probe(mode: int, nontemporal: bool, d_dst: int, d_src: int, nbytes: int, hip_stream: int = 0) -> None:
+    """Streaming kernel of known traffic: mode 0 copy, 1 read, 2 write (raw device addresses)."""
+    vp = lambda x: C.c_void_p(x or None)
+    _check(lib().tns_hbm_probe(mode, 1 if nontemporal else 0, vp(d_dst), vp(d_src), nbytes, vp(hip_stream)), "tns_hbm_probe")
 
 
 def tns_destroy(plan) -> None:
@@ -337,6 +363,13 @@ class Plan:
                     p(out.get("rowptr")), p(out.get("cmp_nbr")), p(out.get("cmp_eid")), p(out.get("cmp_ts")),
                     p(out.get("workspace")), 0 if out.get("workspace") is None else out["workspace"].numel(), stream)
         return out
+
+    def status(self, workspace=None) -> bool:
+        """True if the padding removal of the last step on `workspace` (None: tns_run_static's scratch) timed out."""
+        import torch
+        with torch.cuda.device(self.device):
+            return tns_run_status(self._h, 0 if workspace is None else workspace.data_ptr(),
+                                  torch.cuda.current_stream().cuda_stream)
 
     def run_khop(self, fanouts, targets, t_start, t_end, inst_rowptr=None, delta: float = float("inf"),
                  query_id_base: int = 0):

@@ -15,6 +15,7 @@
 #include "tns_internal.h"
 #include "tns_kernels.h"
 #include "tns_store.h"
+#include "tns_test_hooks.h"
 
 namespace tns {
 thread_local std::string g_err;
@@ -206,7 +207,7 @@ int tns_plan_create(const tns_config* cfg, tns_plan** out) {
     if (cfg->inclusive_end != 0 && cfg->inclusive_end != 1) return fail(TNS_EINVAL, "inclusive_end must be 0 or 1");
     if (cfg->device < 0) return fail(TNS_EINVAL, "negative device ordinal");
     constexpr int32_t kKnownFlags = TNS_FLAG_NO_XCD_REMAP | TNS_FLAG_NO_NODE_SLAB | TNS_FLAG_EDGES_ON_HOST |
-                                    TNS_FLAG_ALL_ON_HOST | TNS_FLAG_DEVICE_INGEST | TNS_FLAG_WIDE_POSITIONS | TNS_FLAG_TEST_LOST_TILE;
+                                    TNS_FLAG_ALL_ON_HOST | TNS_FLAG_DEVICE_INGEST | TNS_FLAG_WIDE_POSITIONS | TNS_TEST_FLAG_LOST_TILE;
     if (cfg->flags & ~kKnownFlags) return fail(TNS_EINVAL, "unknown bit in flags");
     if ((cfg->flags & TNS_FLAG_EDGES_ON_HOST) && (cfg->flags & TNS_FLAG_ALL_ON_HOST))
         return fail(TNS_EINVAL, "TNS_FLAG_EDGES_ON_HOST and TNS_FLAG_ALL_ON_HOST exclude each other");
@@ -494,7 +495,7 @@ static int fill_sample_args(tns_plan* plan, int64_t Q, const int32_t* d_targets,
     a.policy = plan->cfg.policy;
     a.inclusive_end = plan->cfg.inclusive_end;
     a.xcd_remap = (plan->cfg.flags & TNS_FLAG_NO_XCD_REMAP) ? 0 : 1;
-    a.first_ticket = (plan->cfg.flags & TNS_FLAG_TEST_LOST_TILE) ? 1 : 0;
+    a.first_ticket = (plan->cfg.flags & TNS_TEST_FLAG_LOST_TILE) ? 1 : 0;
     a.wide_offsets = (plan->d_edges.used * 32 >= (int64_t(1) << 31) || (plan->cfg.flags & TNS_FLAG_WIDE_POSITIONS)) ? 1 : 0;   // word indices beyond int32
     return TNS_OK;
 }
@@ -519,12 +520,10 @@ static int run_compact(tns_plan* plan, int64_t Q, const int32_t* nbr, const int3
     return TNS_OK;
 }
 
-int tns_run(tns_plan* plan, int64_t Q, const int32_t* d_targets, const float* d_t_start, const float* d_t_end,
-            const int64_t* d_inst_rowptr, int64_t query_id_base, int32_t* d_out_nbr, int32_t* d_out_eid,
-            float* d_out_ts, int32_t* d_out_count, int64_t* d_rowptr, int32_t* d_cmp_nbr, int32_t* d_cmp_eid,
-            float* d_cmp_ts, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
-    g_err.clear();
-    if (!plan) return fail(TNS_EINVAL, "null plan");
+static int run_impl(tns_plan* plan, int64_t Q, const int32_t* d_targets, const float* d_t_start, const float* d_t_end,
+                    const int64_t* d_inst_rowptr, int64_t query_id_base, int32_t* d_out_nbr, int32_t* d_out_eid,
+                    float* d_out_ts, int32_t* d_out_count, int64_t* d_rowptr, int32_t* d_cmp_nbr, int32_t* d_cmp_eid,
+                    float* d_cmp_ts, void* d_workspace, size_t workspace_bytes, bool static_scratch, void* hip_stream) {
     tns::SampleArgs a;
     int rc = fill_sample_args(plan, Q, d_targets, d_t_start, d_t_end, d_inst_rowptr, query_id_base, a);
     if (rc) return rc;
@@ -532,10 +531,10 @@ int tns_run(tns_plan* plan, int64_t Q, const int32_t* d_targets, const float* d_
     // compaction is requested by d_rowptr; with Q == 0 the dense arrays are empty and may be null
     const bool want_cmp = d_rowptr != nullptr;
     if (!want_cmp && (d_cmp_nbr || d_cmp_eid || d_cmp_ts)) return fail(TNS_EINVAL, "pass all four compaction outputs or none");
-    if (want_cmp && (rc = check_compact_args(Q, d_rowptr, d_cmp_nbr, d_cmp_eid, d_cmp_ts, d_workspace, workspace_bytes))) return rc;
 
     DeviceGuard guard(plan->cfg.device);
     if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the plan's device");
+    if (want_cmp && (rc = check_compact_args(Q, d_rowptr, d_cmp_nbr, d_cmp_eid, d_cmp_ts, d_workspace, workspace_bytes))) return rc;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     a.out_nbr = d_out_nbr;
     a.out_eid = d_out_eid;
@@ -561,6 +560,32 @@ int tns_run(tns_plan* plan, int64_t Q, const int32_t* d_targets, const float* d_
     return TNS_OK;
 }
 
+int tns_run(tns_plan* plan, int64_t Q, const int32_t* d_targets, const float* d_t_start, const float* d_t_end,
+            const int64_t* d_inst_rowptr, int64_t query_id_base, int32_t* d_out_nbr, int32_t* d_out_eid,
+            float* d_out_ts, int32_t* d_out_count, int64_t* d_rowptr, int32_t* d_cmp_nbr, int32_t* d_cmp_eid,
+            float* d_cmp_ts, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+    g_err.clear();
+    if (!plan) return fail(TNS_EINVAL, "null plan");
+    return run_impl(plan, Q, d_targets, d_t_start, d_t_end, d_inst_rowptr, query_id_base, d_out_nbr, d_out_eid, d_out_ts,
+                    d_out_count, d_rowptr, d_cmp_nbr, d_cmp_eid, d_cmp_ts, d_workspace, workspace_bytes, false, hip_stream);
+}
+
+int tns_run_status(tns_plan* plan, const void* d_workspace, void* hip_stream, int32_t* timed_out) {
+    g_err.clear();
+    if (!plan || !timed_out) return fail(TNS_EINVAL, "null plan or output pointer");
+    DeviceGuard guard(plan->cfg.device);
+    if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the plan's device");
+    void* ws = const_cast<void*>(d_workspace);
+    if (!ws) return fail(TNS_EINVAL, "null workspace");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    uint32_t word = 0;
+    hipError_t e = hipMemcpyAsync(&word, static_cast<const uint32_t*>(ws) + 1, sizeof(word), hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return fail_hip(e, "reading the status word");
+    *timed_out = word != 0;
+    return TNS_OK;
+}
+
 namespace {
 constexpr int kMaxHops = 8;
 // caps[h] = most queries hop h can have; false if the sizes leave the supported range
@@ -574,6 +599,7 @@ bool khop_caps(int32_t num_hops, const int32_t* fanouts, int64_t Q, int64_t* cap
     }
     return true;
 }
+constexpr size_t kStatusBytes = 256;
 size_t khop_header_bytes(int32_t num_hops, int32_t num_instances) {
     // per hop: the dense total (next hop's query count) and the instance offsets of the next hop
     const size_t per_hop = (size_t)(num_instances + 2) * sizeof(int64_t);
@@ -590,7 +616,7 @@ int tns_workspace_khop(const tns_plan* plan, int32_t num_hops, const int32_t* fa
     // one chained-scan region per hop, so that a single launch can clear them all before the first hop
     size_t scan = 0;
     for (int h = 0; h < num_hops; ++h) scan += tns::compact_workspace_bytes(caps[h]);
-    *bytes = khop_header_bytes(num_hops, plan->cfg.num_instances) + scan;
+    *bytes = kStatusBytes + scan + khop_header_bytes(num_hops, plan->cfg.num_instances);
     return TNS_OK;
 }
 
@@ -622,14 +648,17 @@ int tns_run_khop(tns_plan* plan, int32_t num_hops, const int32_t* fanouts, float
     if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the plan's device");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int32_t I = plan->cfg.num_instances;
-    int64_t* header = static_cast<int64_t*>(d_workspace);
-    unsigned char* scan_ws = static_cast<unsigned char*>(d_workspace) + khop_header_bytes(num_hops, I);
+    // workspace: the status word (second 32-bit word, as in tns_run's workspace), one chained-scan region per
+    // hop, then per hop the dense total and the instance offsets of the next hop
+    unsigned char* scan_ws = static_cast<unsigned char*>(d_workspace) + kStatusBytes;
+    size_t scan = 0;
+    for (int h = 0; h < num_hops; ++h) scan += tns::compact_workspace_bytes(caps[h]);
+    int64_t* header = reinterpret_cast<int64_t*>(scan_ws + scan);
     {
-        size_t scan = 0;
-        for (int h = 0; h < num_hops; ++h) scan += tns::compact_workspace_bytes(caps[h]);
-        const hipError_t e = tns::launch_scan_clear(scan_ws, scan, stream);
+        const hipError_t e = tns::launch_scan_clear(d_workspace, kStatusBytes + scan, stream);
         if (e != hipSuccess) return fail_hip(e, "clearing the chained-scan workspace");
     }
+    a.err_flag = static_cast<uint32_t*>(d_workspace) + 1;   // every hop reports a time-out in the same word
 
     for (int h = 0; h < num_hops; ++h) {
         const tns_hop_buffers& b = hops[h];

@@ -51,6 +51,7 @@ struct SampleArgs {
     int32_t wide_offsets;  // edge array has 2^31 or more entries: 64-bit positions in LDS
     int32_t first_ticket;  // 0; tests of the chained scan's bounded wait pass 1: tile 0 then never exists
     int32_t scan_ready;    // scan_ws is already cleared (multi-hop: one clearing launch for all hops)
+    uint32_t* err_flag;    // where a chained scan whose bounded wait ran out reports it (null: the error word of scan_ws)
 };
 
 struct CompactArgs {

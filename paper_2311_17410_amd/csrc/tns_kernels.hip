@@ -78,7 +78,7 @@ struct ScanWorkspace {
 };
 
 // Sum of the totals of all tiles before `tile` (called by one whole wave).
-__device__ __forceinline__ int64_t lookback_exclusive(ScanWorkspace* ws, int64_t tile, int lane) {
+__device__ __forceinline__ int64_t lookback_exclusive(ScanWorkspace* ws, uint32_t* err_flag, int64_t tile, int lane) {
     int64_t excl = 0;
     int64_t idx = tile - 1;
     int spins = 0;
@@ -99,7 +99,10 @@ __device__ __forceinline__ int64_t lookback_exclusive(ScanWorkspace* ws, int64_t
         const uint64_t needed = first >= kWave - 1 ? ~0ull : ((2ull << first) - 1);    // lanes 0..first
         if (not_ready & needed) {
             if (++spins > kSpinLimit) {
-                if (lane == 0) atomicExch(&ws->error, 1u);
+                // reported before this tile publishes anything, so that whoever builds on its (wrong)
+                // prefix can see the flag
+                if (lane == 0) atomicExch(err_flag, 1u);
+                __threadfence();
                 return excl;
             }
             __builtin_amdgcn_s_sleep(16);      // ~0.4 us between polls: late tiles are late by microseconds
@@ -645,7 +648,7 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256, FUSED ? 4 : 6) tns_sample_
                 __hip_atomic_store(&ws->status[tile], kStTotal | (uint64_t)wg_total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         };
         auto chain = [&](int32_t wg_total) {      // one wave: look back for the tile's offset, publish the prefix
-            const int64_t excl = tile > 0 ? lookback_exclusive(ws, tile, lane) : 0;
+            const int64_t excl = tile > 0 ? lookback_exclusive(ws, p.err_flag, tile, lane) : 0;
             if (lane == 0) {
                 __hip_atomic_store(&ws->status[tile], kStPrefix | (uint64_t)(excl + wg_total), __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
@@ -656,8 +659,14 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256, FUSED ? 4 : 6) tns_sample_
             if (q < Q) {
                 __builtin_nontemporal_store(row, &p.rowptr[q]);
                 if (q == Q - 1) {
-                    p.rowptr[Q] = row + k;
-                    if (p.total_out) *p.total_out = row + k;
+                    // The last query's tile has looked back over every other tile.  If any wait ran into
+                    // its bound the dense rows are not valid: the total then reads 0, so that a hop chained
+                    // to this one has no queries.
+                    __threadfence();
+                    const bool bad = __hip_atomic_load(p.err_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0;
+                    const int64_t tot = bad ? 0 : row + k;
+                    p.rowptr[Q] = tot;
+                    if (p.total_out) *p.total_out = tot;
                 }
             }
         };
@@ -751,7 +760,7 @@ __global__ void __launch_bounds__(256) tns_count_tile_sums(const int32_t* __rest
 __global__ void __launch_bounds__(1024) tns_scan_tile_sums(const int32_t* __restrict__ tile_sums, int64_t num_tiles,
                                                            int64_t* __restrict__ tile_offs, int64_t* __restrict__ rowptr,
                                                            int64_t Q, const int64_t* __restrict__ Q_dev,
-                                                           int64_t* __restrict__ total_out) {
+                                                           int64_t* __restrict__ total_out, uint32_t* __restrict__ ws_head) {
     __shared__ int32_t s_w[16];
     __shared__ int64_t s_carry;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -780,6 +789,8 @@ __global__ void __launch_bounds__(1024) tns_scan_tile_sums(const int32_t* __rest
         if (Q_dev) Q = min(Q, *Q_dev);
         rowptr[Q < 0 ? 0 : Q] = s_carry;          // end of rowptr for the actual number of queries
         if (total_out) *total_out = s_carry;
+        ws_head[0] = 0;                           // the workspace's status word: no chained scan ran, nothing timed out
+        ws_head[1] = 0;
     }
 }
 
@@ -873,8 +884,10 @@ hipError_t launch_sample_t(const SampleArgs& a, hipStream_t stream) {
     }
     if (grid <= 0) return hipGetLastError();
     const size_t lds = chunk * waves;
+    SampleArgs b = a;
+    if (FUSED && !b.err_flag) b.err_flag = &static_cast<ScanWorkspace*>(a.scan_ws)->error;
     hipLaunchKernelGGL((tns_sample_kernel<POLICY, INCL, pos_t, COUNT, FUSED>), dim3((unsigned)grid), dim3(waves * kWave),
-                       lds, stream, a, stride, magic_for(a.fanout), gshift, (uint32_t)chunk);
+                       lds, stream, b, stride, magic_for(a.fanout), gshift, (uint32_t)chunk);
     return hipGetLastError();
 }
 
@@ -920,7 +933,9 @@ hipError_t launch_hop_inst_rowptr(const int64_t* cur, const int64_t* rowptr, int
 
 hipError_t launch_compact(const CompactArgs& a, hipStream_t stream) {
     const int64_t tiles = (a.Q + kCompactTile - 1) / kCompactTile;
-    unsigned char* ws = static_cast<unsigned char*>(a.workspace);
+    // the first 256 bytes of a workspace hold the status word of the step (read by tns_run_status)
+    uint32_t* ws_head = static_cast<uint32_t*>(a.workspace);
+    unsigned char* ws = static_cast<unsigned char*>(a.workspace) + 256;
     int32_t* sums = reinterpret_cast<int32_t*>(ws);
     const size_t sums_bytes = ((size_t)tiles * sizeof(int32_t) + 255) & ~size_t(255);
     int64_t* offs = reinterpret_cast<int64_t*>(ws + sums_bytes);
@@ -929,7 +944,7 @@ hipError_t launch_compact(const CompactArgs& a, hipStream_t stream) {
         hipLaunchKernelGGL(tns_count_tile_sums, dim3((unsigned)tiles), dim3(256), 0, stream, a.count, a.Q, a.Q_dev, sums);
     }
     hipLaunchKernelGGL(tns_scan_tile_sums, dim3(1), dim3(1024), 0, stream, sums, tiles, offs, a.rowptr, a.Q, a.Q_dev,
-                       a.total_out);
+                       a.total_out, ws_head);
     if (tiles > 0) {
         hipLaunchKernelGGL(tns_compact_scatter, dim3((unsigned)tiles), dim3(256), 0, stream, a, offs,
                            magic_for(a.fanout));

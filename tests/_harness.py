@@ -30,10 +30,7 @@ def gpu_sample(plan, targets, t_start, t_end, inst_rowptr=None, compact=True, qu
     res = dict(nbr=out["nbr"].cpu().numpy().reshape(Q, f), eid=out["eid"].cpu().numpy().reshape(Q, f),
                ts=out["ts"].cpu().numpy().reshape(Q, f), count=out["count"].cpu().numpy())
     if compact:
-        # second 32-bit word of the workspace: set only if the chained scan's bounded wait ran out
-        # (with the edge data in host memory the two steps run apart and the word means nothing)
-        if not plan.flags & 12:
-            assert int(out["workspace"][4:8].view(torch.int32).item()) == 0, "chained scan reported a timeout"
+        assert not plan.status(out["workspace"]), "chained scan reported a timeout"
         rowptr = out["rowptr"].cpu().numpy()
         total = int(rowptr[-1])
         res.update(rowptr=rowptr, cmp_nbr=out["cmp_nbr"][:total].cpu().numpy(),

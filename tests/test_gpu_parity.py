@@ -184,14 +184,15 @@ def test_bounded_wait_of_the_chained_scan_ends(B):
     import torch
     st = W.tiny_stream(17, 40000, 500, 4096, ties=False)
     wl = wl_of(st, fanout=10)
-    plan = build_plan(B, wl, 0, flags=B.TNS_FLAG_TEST_LOST_TILE)
+    plan = build_plan(B, wl, 0, flags=B.TNS_TEST_FLAG_LOST_TILE)
     dev = torch.device("cuda", 0)
     d_t, d_e = torch.from_numpy(st.src).to(dev), torch.from_numpy(st.ts).to(dev)
     t0 = time.time()
     out = plan.run(d_t, None, d_e)
     torch.cuda.synchronize()
     assert time.time() - t0 < 60
-    assert int(out["workspace"][4:8].view(torch.int32).item()) == 1
+    assert plan.status(out["workspace"]), "the time-out must be reported"
+    assert int(out["rowptr"][-1].item()) == 0, "after a time-out the dense total reads 0"
     plan.close()
 
 
@@ -277,21 +278,14 @@ def test_deleted_edges_and_nodes_are_ignored(B, oracle_lib, policy):
 # ---- multi-hop --------------------------------------------------------------------------------
 
 def oracle_khop(oracle, wl, targets, t_start, t_end, inst_rowptr, fanouts, delta, policy, seed, base=0):
-    """Hop h+1 takes the dense result of hop h as its queries: target = sampled neighbour, window
-    end = sampled edge's time, start = end - delta (fp32).  Returns per hop (padded result, rowptr,
-    number of queries)."""
-    out, cap = [], len(targets)
-    for f in fanouts:
-        ref = oracle_sample(oracle, wl, targets, t_start, t_end, inst_rowptr, f, policy, 0, seed, query_id_base=base)
-        rowptr, cn, ce, ct = oracle.compact(ref)
-        out.append((ref, rowptr, cn, ce, ct))
-        if inst_rowptr is not None:
-            inst_rowptr = rowptr[inst_rowptr]
-        targets, t_end = cn, ct
-        t_start = None if np.isinf(delta) else (ct - np.float32(delta)).astype(np.float32)
-        base += cap
-        cap *= f
-    return out
+    """The chained reference (oracle/khop_oracle.py) over the workload's instances, as tuples per hop."""
+    from oracle import khop_oracle
+    adjs = [oracle.Adjacency(st.num_nodes, st.src, st.dst, st.ts) for st in wl.streams]
+    hops = khop_oracle.khop(adjs, targets, t_start, t_end, inst_rowptr, fanouts, delta=delta, policy=policy, seed=seed,
+                            query_id_base=base, threads=8)
+    for a in adjs:
+        a.close()
+    return [(h["padded"], h["rowptr"], h["cmp_nbr"], h["cmp_eid"], h["cmp_ts"]) for h in hops]
 
 
 @pytest.mark.parametrize("policy", [0, 1])
@@ -306,6 +300,7 @@ def test_khop_matches_chained_oracle(B, oracle_lib, policy, fanouts, delta):
     d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
     hops, ws = plan.run_khop(fanouts, d(targets), d(t_start), d(t_end), delta=delta, query_id_base=1000)
     torch.cuda.synchronize()
+    assert not plan.status(ws), "a hop's chained scan reported a timeout"
     ref = oracle_khop(oracle_lib, wl, targets, t_start, t_end, None, fanouts, delta, policy, 9, base=1000)
     n = len(targets)
     for h, (r, rowptr, cn, ce, ct) in enumerate(ref):
@@ -334,6 +329,7 @@ def test_khop_batched_instances_and_c2(B, oracle_lib):
         fanouts = [10, 10] if wl.num_instances > 1 else [10, 5]
         hops, ws = plan.run_khop(fanouts, d(targets), None, d(t_end), None if rp is None else d(rp))
         torch.cuda.synchronize()
+        assert not plan.status(ws), "a hop's chained scan reported a timeout"
         ref = oracle_khop(oracle_lib, wl, targets, None, t_end, rp, fanouts, float("inf"), 0, 0)
         n = len(targets)
         for h, (r, rowptr_h, cn, ce, ct) in enumerate(ref):

@@ -214,11 +214,27 @@ TNS_API int tns_run(tns_plan *plan, int64_t Q, const int32_t *d_targets, const f
 
 /*
  * Whether a bounded wait of the padding removal ran out in the last tns_run, tns_compact, tns_run_khop
- * (any hop; the following hops then had no queries) that used `d_workspace` (DEVICE).  Waits for `hip_stream`, copies one
+ * (any hop; the following hops then had no queries) or tns_run_static that used `d_workspace` (DEVICE;
+ * NULL = the static scratch of tns_run_static on the plan's device).  Waits for `hip_stream`, copies one
  * word to the host; *timed_out (HOST) receives 0 or 1.  Not a step of the paper's method: the error
  * report of this implementation's single-pass scan.
  */
 TNS_API int tns_run_status(tns_plan *plan, const void *d_workspace, void *hip_stream, int32_t *timed_out);
+
+/*
+ * For callers that cannot allocate device memory or own no workspace (code under HIP graph capture,
+ * serving loops, harnesses that forbid allocation): tns_run with padding removal (d_rowptr and the
+ * dense arrays are required), its scan state kept in a static device array of the library instead of
+ * a caller's workspace.  Arguments and results as tns_run.  At most 2^24 queries per call (TNS_ESIZE
+ * beyond; the array is 2 MiB + 512 bytes per GPU, held until the process ends).  Calls no allocation
+ * routine.  All calls on one GPU share the array: calls that overlap in time on one GPU (different
+ * streams, different plans) race; on one stream they are ordered.  Status: tns_run_status with a NULL
+ * workspace.
+ */
+TNS_API int tns_run_static(tns_plan *plan, int64_t Q, const int32_t *d_targets, const float *d_t_start,
+            const float *d_t_end, const int64_t *d_inst_rowptr, int64_t query_id_base,
+            int32_t *d_out_nbr, int32_t *d_out_eid, float *d_out_ts, int32_t *d_out_count,
+            int64_t *d_rowptr, int32_t *d_cmp_nbr, int32_t *d_cmp_eid, float *d_cmp_ts, void *hip_stream);
 
 /*
  * Multi-hop sampling (section 4.2: the process is repeated per layer, the nodes sampled in one

@@ -27,7 +27,7 @@ TNS_FLAG_DEVICE_INGEST = 16
 TNS_FLAG_WIDE_POSITIONS = 32
 TNS_TEST_FLAG_LOST_TILE = 64      # csrc/tns_test_hooks.h: for the library's own tests, not in the public header
 
-EXPORTS = ["tns_plan_create", "tns_set_sampler", "tns_add_edges", "tns_add_edges_device", "tns_delete_edges", "tns_delete_nodes", "tns_commit", "tns_workspace", "tns_run", "tns_run_status", "tns_workspace_khop", "tns_run_khop", "tns_compact", "tns_traffic_model", "tns_stats",
+EXPORTS = ["tns_plan_create", "tns_set_sampler", "tns_add_edges", "tns_add_edges_device", "tns_delete_edges", "tns_delete_nodes", "tns_commit", "tns_workspace", "tns_run", "tns_run_status", "tns_run_static", "tns_workspace_khop", "tns_run_khop", "tns_compact", "tns_traffic_model", "tns_stats",
            "tns_node_blocks", "tns_hbm_probe", "tns_destroy", "tns_strerror", "tns_last_error"]
 
 
@@ -95,6 +95,8 @@ def lib():
         L.tns_run.restype = C.c_int
         L.tns_run_status.argtypes = [vp, vp, vp, C.POINTER(C.c_int32)]
         L.tns_run_status.restype = C.c_int
+        L.tns_run_static.argtypes = [vp, C.c_int64, vp, vp, vp, vp, C.c_int64, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.tns_run_static.restype = C.c_int
         L.tns_workspace_khop.argtypes = [vp, C.c_int32, i32p, C.c_int64, C.POINTER(C.c_size_t)]
         L.tns_workspace_khop.restype = C.c_int
         L.tns_run_khop.argtypes = [vp, C.c_int32, i32p, C.c_float, C.c_int64, vp, vp, vp, vp, C.c_int64,
@@ -207,6 +209,16 @@ def tns_run_status(plan, d_workspace: int = 0, hip_stream: int = 0) -> bool:
     _check(lib().tns_run_status(plan, C.c_void_p(d_workspace or None), C.c_void_p(hip_stream or None), C.byref(out)),
            "tns_run_status")
     return bool(out.value)
+
+
+def tns_run_static(plan, Q: int, d_targets: int, d_t_start: int, d_t_end: int, d_inst_rowptr: int, query_id_base: int,
+                   d_out_nbr: int, d_out_eid: int, d_out_ts: int, d_out_count: int, d_rowptr: int, d_cmp_nbr: int,
+                   d_cmp_eid: int, d_cmp_ts: int, hip_stream: int = 0) -> None:
+    """tns_run with padding removal on the library's static scratch (no workspace argument)."""
+    vp = lambda x: C.c_void_p(x or None)
+    _check(lib().tns_run_static(plan, Q, vp(d_targets), vp(d_t_start), vp(d_t_end), vp(d_inst_rowptr), query_id_base,
+                                vp(d_out_nbr), vp(d_out_eid), vp(d_out_ts), vp(d_out_count), vp(d_rowptr), vp(d_cmp_nbr),
+                                vp(d_cmp_eid), vp(d_cmp_ts), vp(hip_stream)), "tns_run_static")
 
 
 def tns_workspace_khop(plan, fanouts, Q: int) -> int:

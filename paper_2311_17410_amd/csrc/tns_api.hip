@@ -6,6 +6,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <memory>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -192,6 +193,32 @@ struct DeviceTemp {
 };
 
 }  // namespace
+
+// ---- entry point for callers that cannot allocate: the workspace is a static device array ----
+//
+// Each GPU the library runs on holds its own copy of the array for the life of the process.  Host code never
+// uses the array's name as an address: the per-device address comes from hipGetSymbolAddress, once.
+constexpr int64_t kStaticMaxQueries = int64_t(1) << 24;
+constexpr size_t kStaticScratchBytes = (size_t(2) << 20) + 512;   // = tns_workspace() for 2^24 queries
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+// Address of `scratch` on device `dev` (which must be the current device).
+static int static_scratch_of(int dev, void** out) {
+    if (dev < 0 || dev >= kMaxDevices) return fail(TNS_EINVAL, "device ordinal beyond the static scratch table");
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) return fail_hip(e == hipSuccess ? hipErrorInvalidSymbol : e, "locating the static scratch array");
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return TNS_OK;
+}
 
 extern "C" {
 
@@ -427,6 +454,12 @@ int tns_commit(tns_plan* plan, void* hip_stream) {
     DeviceGuard guard(plan->cfg.device);
     if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the plan's device");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    {
+        // set-up: find this device's copy of the static scratch array (used by tns_run_static)
+        void* unused = nullptr;
+        const int rc0 = static_scratch_of(plan->cfg.device, &unused);
+        if (rc0) return rc0;
+    }
     if (plan->dev) return ensure_device_store(plan, stream);   // nothing to upload: the store lives on the device
     tns::Store& s = *plan->store;
     int rc;
@@ -534,6 +567,11 @@ static int run_impl(tns_plan* plan, int64_t Q, const int32_t* d_targets, const f
 
     DeviceGuard guard(plan->cfg.device);
     if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the plan's device");
+    if (static_scratch && want_cmp) {
+        if (Q > kStaticMaxQueries) return fail(TNS_ESIZE, "tns_run_static serves at most 2^24 queries per call");
+        if ((rc = static_scratch_of(plan->cfg.device, &d_workspace))) return rc;
+        workspace_bytes = kStaticScratchBytes;
+    }
     if (want_cmp && (rc = check_compact_args(Q, d_rowptr, d_cmp_nbr, d_cmp_eid, d_cmp_ts, d_workspace, workspace_bytes))) return rc;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     a.out_nbr = d_out_nbr;
@@ -570,13 +608,25 @@ int tns_run(tns_plan* plan, int64_t Q, const int32_t* d_targets, const float* d_
                     d_out_count, d_rowptr, d_cmp_nbr, d_cmp_eid, d_cmp_ts, d_workspace, workspace_bytes, false, hip_stream);
 }
 
+int tns_run_static(tns_plan* plan, int64_t Q, const int32_t* d_targets, const float* d_t_start, const float* d_t_end,
+                   const int64_t* d_inst_rowptr, int64_t query_id_base, int32_t* d_out_nbr, int32_t* d_out_eid,
+                   float* d_out_ts, int32_t* d_out_count, int64_t* d_rowptr, int32_t* d_cmp_nbr, int32_t* d_cmp_eid,
+                   float* d_cmp_ts, void* hip_stream) {
+    g_err.clear();
+    if (!plan) return fail(TNS_EINVAL, "null plan");
+    if (!d_rowptr) return fail(TNS_EINVAL, "tns_run_static is the variant with padding removal: d_rowptr is required");
+    return run_impl(plan, Q, d_targets, d_t_start, d_t_end, d_inst_rowptr, query_id_base, d_out_nbr, d_out_eid, d_out_ts,
+                    d_out_count, d_rowptr, d_cmp_nbr, d_cmp_eid, d_cmp_ts, nullptr, 0, true, hip_stream);
+}
+
 int tns_run_status(tns_plan* plan, const void* d_workspace, void* hip_stream, int32_t* timed_out) {
     g_err.clear();
     if (!plan || !timed_out) return fail(TNS_EINVAL, "null plan or output pointer");
     DeviceGuard guard(plan->cfg.device);
     if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the plan's device");
     void* ws = const_cast<void*>(d_workspace);
-    if (!ws) return fail(TNS_EINVAL, "null workspace");
+    int rc;
+    if (!ws && (rc = static_scratch_of(plan->cfg.device, &ws))) return rc;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     uint32_t word = 0;
     hipError_t e = hipMemcpyAsync(&word, static_cast<const uint32_t*>(ws) + 1, sizeof(word), hipMemcpyDeviceToHost, stream);

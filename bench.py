@@ -100,6 +100,9 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="accepted for the recorded profile commands: the plain 1 GiB device copy of known traffic "
                          "now always runs (it also gives the box's streaming ceiling)")
+    ap.add_argument("--layout", default="prefix", choices=["prefix", "blocks"],
+                    help="prefix: a node's first 38 edge slots in its own line + up to three extension lines (default for "
+                         "device-resident, host-built stores); blocks: every block placed on its own, records in the node line")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU oracle time budget (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -126,13 +129,17 @@ def main() -> int:
     wl = W.by_name(args.workload, **kw)
     Q, f = wl.total_edges, wl.fanout
 
-    log(f"ingesting {Q} edges into {wl.num_instances} instance(s), tau={wl.tau}")
+    if args.placement != "hbm" or args.ingest == "device":
+        args.layout = "blocks"          # the prefix layout is for host-built, device-resident stores
+    node_entry_bytes = 32 if args.layout == "prefix" else 16
+    log(f"ingesting {Q} edges into {wl.num_instances} instance(s), tau={wl.tau}, layout={args.layout}")
     t0 = time.time()
     plan = B.Plan(wl.num_nodes, f, policy=policy, block_threshold=wl.tau, num_instances=wl.num_instances,
                   seed=wl.seed,
                   flags=(B.TNS_FLAG_NO_XCD_REMAP if args.no_remap else 0)
                   | {"hbm": 0, "hybrid": B.TNS_FLAG_EDGES_ON_HOST, "host": B.TNS_FLAG_ALL_ON_HOST}[args.placement]
-                  | (B.TNS_FLAG_DEVICE_INGEST if args.ingest == "device" else 0))
+                  | (B.TNS_FLAG_DEVICE_INGEST if args.ingest == "device" else 0)
+                  | (B.TNS_FLAG_PREFIX_LAYOUT if args.layout == "prefix" else 0))
     last = time.time()
     for i, st in enumerate(wl.streams):
         if args.ingest == "device":
@@ -187,7 +194,7 @@ def main() -> int:
     torch.cuda.synchronize()
     n_nodes, n_blocks, n_probes, n_edges = (int(x) for x in counters.cpu())
     q_in = 8 + (4 if d_tb is not None else 0) + (0 if d_rp is None else 0)
-    bytes_sample = {"queries": q_in * Q, "node_entries": 16 * n_nodes, "block_records": 16 * n_blocks,
+    bytes_sample = {"queries": q_in * Q, "node_entries": node_entry_bytes * n_nodes, "block_records": 16 * n_blocks,
                     "timestamp_probes": 4 * n_probes, "edge_gather": 12 * n_edges, "padded_write": (12 * f + 4) * Q}
     alg_sample = sum(bytes_sample.values())
     alg_compact = (4 + 4 + 12 * f) * Q + 8 * (Q + 1) + 12 * n_edges     # counts twice, padded once, rowptr, dense
@@ -256,7 +263,7 @@ def main() -> int:
         torch.cuda.synchronize()
         o_ms = evo[0].elapsed_time(evo[1]) / 5
         on, ob, op_, oe = (int(x) for x in counters.cpu())
-        o_alg = q_in * Q + 16 * on + 16 * ob + 4 * op_ + 12 * oe + (12 * f + 4) * Q + 12 * oe + 8 * (Q + 1)
+        o_alg = q_in * Q + node_entry_bytes * on + 16 * ob + 4 * op_ + 12 * oe + (12 * f + 4) * Q + 12 * oe + 8 * (Q + 1)
         other = {"policy": other_name, "ms_per_step": o_ms, "value": Q / (o_ms * 1e-3), "unit": "elements/s",
                  "algorithmic_bytes_per_launch": o_alg, "frac": o_alg / (o_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "steps": 5}
         plan.set_sampler(f, policy, 0, wl.seed)
@@ -283,7 +290,7 @@ def main() -> int:
         "config": {"workload": f"{wl.name}: {wl.description}; query i = (src[i], -inf, ts[i]); f={f}, tau={wl.tau}, "
                                f"policy={args.policy}, window={'0.25 span' if args.windowed else 'unbounded'}",
                    "queries": Q, "instances": wl.num_instances, "nodes_per_instance": wl.num_nodes,
-                   "placement": args.placement, "ingest": args.ingest},
+                   "placement": args.placement, "ingest": args.ingest, "layout": args.layout},
         "roofline": {"bound": "hbm", "kernel": "tns_sample_kernel (padding removal fused)" if args.placement == "hbm" else "tns_sample_kernel + tns_compact kernels", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "moved": moved, "copy_ceiling_GBs": copy_gbs,

@@ -77,7 +77,16 @@ enum {
     /* Keep edge positions as 64-bit values inside the kernels even while the edge array is small.  The
        library switches to them by itself once the array passes 2^31 four-byte words (8 GiB); the
        flag exists so that tests reach that code without such a store. */
-    TNS_FLAG_WIDE_POSITIONS = 32
+    TNS_FLAG_WIDE_POSITIONS = 32,
+    /* (64 is taken by a hook of the library's own tests.)
+       Prefix layout: another placement of the same store (section 4.1 fixes what a node entry and a
+       block hold, not where they lie).  A node's first eight edge slots share the 128-byte line of
+       its table entry and its next thirty sit in up to three lines found from that entry, so that a
+       query on a node of a few dozen edges reads one to three lines.  Block capacities, list
+       lengths, tns_stats and tns_node_blocks are those of the default layout; sampling results are
+       identical.  Host-built, device-resident stores only (not with the host placements,
+       TNS_FLAG_DEVICE_INGEST or TNS_FLAG_NO_NODE_SLAB). */
+    TNS_FLAG_PREFIX_LAYOUT = 128
 };
 
 typedef struct {

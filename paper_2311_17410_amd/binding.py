@@ -25,6 +25,7 @@ TNS_FLAG_EDGES_ON_HOST = 4
 TNS_FLAG_ALL_ON_HOST = 8
 TNS_FLAG_DEVICE_INGEST = 16
 TNS_FLAG_WIDE_POSITIONS = 32
+TNS_FLAG_PREFIX_LAYOUT = 128
 TNS_TEST_FLAG_LOST_TILE = 64      # csrc/tns_test_hooks.h: for the library's own tests, not in the public header
 
 EXPORTS = ["tns_plan_create", "tns_set_sampler", "tns_add_edges", "tns_add_edges_device", "tns_delete_edges", "tns_delete_nodes", "tns_commit", "tns_workspace", "tns_run", "tns_run_status", "tns_run_static", "tns_workspace_khop", "tns_run_khop", "tns_compact", "tns_traffic_model", "tns_stats",

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtns.so")
-SOURCES = ["tns_api.hip", "tns_kernels.hip", "tns_store.cpp", "tns_cache.hip", "tns_ingest.hip", "tns_probe.hip"]
+SOURCES = ["tns_api.hip", "tns_kernels.hip", "tns_store.cpp", "tns_pstore.cpp", "tns_kernels_prefix.hip", "tns_cache.hip", "tns_ingest.hip", "tns_probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = [

@@ -15,6 +15,7 @@
 #include "tns_ingest.h"
 #include "tns_internal.h"
 #include "tns_kernels.h"
+#include "tns_pstore.h"
 #include "tns_store.h"
 #include "tns_test_hooks.h"
 
@@ -74,6 +75,8 @@ struct tns_plan {
     tns_config cfg;
     std::unique_ptr<tns::Store> store;          // host builder (null for a device-built store)
     std::unique_ptr<DeviceStore> dev;           // device builder (null otherwise)
+    std::unique_ptr<tns::PrefixStore> pstore;   // host builder of the prefix layout (TNS_FLAG_PREFIX_LAYOUT; null otherwise)
+    DeviceArray<tns::StoreLine> d_lines;        // prefix layout: node lines and edge lines in one array
     DeviceArray<tns::NodeLine> d_nodes;
     DeviceArray<tns::BlockRec> d_dir;
     DeviceArray<uint32_t> d_dir_cum;            // per directory record: the node's edges in older blocks
@@ -234,13 +237,17 @@ int tns_plan_create(const tns_config* cfg, tns_plan** out) {
     if (cfg->inclusive_end != 0 && cfg->inclusive_end != 1) return fail(TNS_EINVAL, "inclusive_end must be 0 or 1");
     if (cfg->device < 0) return fail(TNS_EINVAL, "negative device ordinal");
     constexpr int32_t kKnownFlags = TNS_FLAG_NO_XCD_REMAP | TNS_FLAG_NO_NODE_SLAB | TNS_FLAG_EDGES_ON_HOST |
-                                    TNS_FLAG_ALL_ON_HOST | TNS_FLAG_DEVICE_INGEST | TNS_FLAG_WIDE_POSITIONS | TNS_TEST_FLAG_LOST_TILE;
+                                    TNS_FLAG_ALL_ON_HOST | TNS_FLAG_DEVICE_INGEST | TNS_FLAG_WIDE_POSITIONS | TNS_TEST_FLAG_LOST_TILE |
+                                    TNS_FLAG_PREFIX_LAYOUT;
     if (cfg->flags & ~kKnownFlags) return fail(TNS_EINVAL, "unknown bit in flags");
     if ((cfg->flags & TNS_FLAG_EDGES_ON_HOST) && (cfg->flags & TNS_FLAG_ALL_ON_HOST))
         return fail(TNS_EINVAL, "TNS_FLAG_EDGES_ON_HOST and TNS_FLAG_ALL_ON_HOST exclude each other");
     if ((cfg->flags & TNS_FLAG_DEVICE_INGEST) &&
         (cfg->flags & (TNS_FLAG_EDGES_ON_HOST | TNS_FLAG_ALL_ON_HOST | TNS_FLAG_NO_NODE_SLAB)))
         return fail(TNS_EINVAL, "TNS_FLAG_DEVICE_INGEST cannot be combined with host placement or TNS_FLAG_NO_NODE_SLAB");
+    if ((cfg->flags & TNS_FLAG_PREFIX_LAYOUT) &&
+        (cfg->flags & (TNS_FLAG_EDGES_ON_HOST | TNS_FLAG_ALL_ON_HOST | TNS_FLAG_DEVICE_INGEST | TNS_FLAG_NO_NODE_SLAB)))
+        return fail(TNS_EINVAL, "TNS_FLAG_PREFIX_LAYOUT cannot be combined with host placement, TNS_FLAG_DEVICE_INGEST or TNS_FLAG_NO_NODE_SLAB");
     try {
         std::unique_ptr<tns_plan> p(new tns_plan());
         p->cfg = *cfg;
@@ -256,7 +263,8 @@ int tns_plan_create(const tns_config* cfg, tns_plan** out) {
             sc.tau = cfg->block_threshold;
             sc.sizing = cfg->sizing;
             sc.node_slab = !(cfg->flags & TNS_FLAG_NO_NODE_SLAB);
-            p->store.reset(new tns::Store(sc));
+            if (cfg->flags & TNS_FLAG_PREFIX_LAYOUT) p->pstore.reset(new tns::PrefixStore(sc));
+            else p->store.reset(new tns::Store(sc));
         }
         *out = p.release();
     } catch (const std::bad_alloc&) {
@@ -285,7 +293,8 @@ int tns_add_edges(tns_plan* plan, int32_t instance, const int32_t* src, const in
     if (plan->dev) return fail(TNS_ESTATE, "this plan's store is built on the device: use tns_add_edges_device");
     try {
         std::string err;
-        const int rc = plan->store->add_edges(instance, src, dst, ts, eid, m, err);
+        const int rc = plan->pstore ? plan->pstore->add_edges(instance, src, dst, ts, eid, m, err)
+                                    : plan->store->add_edges(instance, src, dst, ts, eid, m, err);
         if (rc != TNS_OK) g_err = err;
         return rc;
     } catch (const std::bad_alloc&) {
@@ -416,9 +425,13 @@ int tns_delete_edges(tns_plan* plan, int32_t instance, const int32_t* src, const
         if (num_deleted) *num_deleted = (int64_t)st.counter;
         return TNS_OK;
     }
-    tns::Store& s = *plan->store;
     int64_t hit = 0;
-    for (int64_t i = 0; i < m; ++i) hit += s.delete_edge(instance, src[i], eid[i]);
+    if (plan->pstore) {
+        for (int64_t i = 0; i < m; ++i) hit += plan->pstore->delete_edge(instance, src[i], eid[i]);
+    } else {
+        tns::Store& s = *plan->store;
+        for (int64_t i = 0; i < m; ++i) hit += s.delete_edge(instance, src[i], eid[i]);
+    }
     if (num_deleted) *num_deleted = hit;
     return TNS_OK;
 }
@@ -443,6 +456,10 @@ int tns_delete_nodes(tns_plan* plan, int32_t instance, const int32_t* nodes, int
         if (e != hipSuccess) return fail_hip(e, "marking nodes on the device");
         return TNS_OK;
     }
+    if (plan->pstore) {
+        for (int64_t i = 0; i < m; ++i) plan->pstore->set_node_deleted(instance, nodes[i], deleted != 0);
+        return TNS_OK;
+    }
     tns::Store& s = *plan->store;
     for (int64_t i = 0; i < m; ++i) s.set_node_deleted(instance, nodes[i], deleted != 0);
     return TNS_OK;
@@ -461,6 +478,23 @@ int tns_commit(tns_plan* plan, void* hip_stream) {
         if (rc0) return rc0;
     }
     if (plan->dev) return ensure_device_store(plan, stream);   // nothing to upload: the store lives on the device
+    if (plan->pstore) {
+        tns::PrefixStore& s = *plan->pstore;
+        int rc;
+        if ((rc = ensure_capacity(plan->d_lines, std::max<int64_t>(s.lines.size(), 1), s.lines, "allocating the store"))) return rc;
+        if ((rc = ensure_capacity(plan->d_dir, std::max<int64_t>(s.dir.size(), 1), s.dir, "allocating the block directory"))) return rc;
+        if ((rc = ensure_capacity(plan->d_dir_cum, std::max<int64_t>(s.dir_cum.size(), 1), s.dir_cum, "allocating the block directory"))) return rc;
+        if ((rc = upload_dirty(plan->d_lines, s.lines, stream, "uploading the store"))) return rc;
+        if ((rc = upload_dirty(plan->d_dir, s.dir, stream, "uploading the block directory"))) return rc;
+        if ((rc = upload_dirty(plan->d_dir_cum, s.dir_cum, stream, "uploading the block directory"))) return rc;
+        const hipError_t e = hipStreamSynchronize(stream);
+        if (e != hipSuccess) return fail_hip(e, "waiting for the upload");
+        s.lines.clear_dirty();
+        s.dir.clear_dirty();
+        s.dir_cum.clear_dirty();
+        plan->committed = true;
+        return TNS_OK;
+    }
     tns::Store& s = *plan->store;
     int rc;
     // at least one element each, so that the kernels always get valid base pointers
@@ -514,6 +548,15 @@ static int fill_sample_args(tns_plan* plan, int64_t Q, const int32_t* d_targets,
     a.dir = plan->d_dir.ptr;
     a.dir_cum = plan->d_dir_cum.ptr;
     a.edges = reinterpret_cast<const uint32_t*>(plan->d_edges.ptr);
+    if (plan->pstore) {
+        a.nodes = nullptr;
+        a.edges = reinterpret_cast<const uint32_t*>(plan->d_lines.ptr);
+        a.prefix_layout = 1;
+        static const int env_waves = [] { const char* v = std::getenv("TNS_PREFIX_WAVES"); return v ? std::atoi(v) : 0; }();
+        a.prefix_waves = env_waves;     // tuning aid: waves per workgroup of the prefix-layout kernel
+        static const int env_exp = [] { const char* v = std::getenv("TNS_EXP"); return v ? std::atoi(v) : 0; }();
+        a.exp = env_exp;
+    }
     a.targets = d_targets;
     a.t_start = d_t_start;
     a.t_end = d_t_end;
@@ -529,7 +572,8 @@ static int fill_sample_args(tns_plan* plan, int64_t Q, const int32_t* d_targets,
     a.inclusive_end = plan->cfg.inclusive_end;
     a.xcd_remap = (plan->cfg.flags & TNS_FLAG_NO_XCD_REMAP) ? 0 : 1;
     a.first_ticket = (plan->cfg.flags & TNS_TEST_FLAG_LOST_TILE) ? 1 : 0;
-    a.wide_offsets = (plan->d_edges.used * 32 >= (int64_t(1) << 31) || (plan->cfg.flags & TNS_FLAG_WIDE_POSITIONS)) ? 1 : 0;   // word indices beyond int32
+    const int64_t edge_lines = plan->pstore ? plan->d_lines.used : plan->d_edges.used;
+    a.wide_offsets = (edge_lines * 32 >= (int64_t(1) << 31) || (plan->cfg.flags & TNS_FLAG_WIDE_POSITIONS)) ? 1 : 0;   // word indices beyond int32
     return TNS_OK;
 }
 
@@ -812,6 +856,24 @@ int tns_stats(const tns_plan* plan, int32_t instance, tns_stats_t* out) {
         *out = r;
         return TNS_OK;
     }
+    if (plan->pstore) {
+        const tns::PrefixStore& s = *plan->pstore;
+        for (int32_t i = i0; i < i1; ++i) {
+            const tns::InstanceTotals& t = s.totals(i);
+            r.num_blocks += t.blocks;
+            r.num_edges += t.edges;
+            r.wasted_slots += t.slots - t.edges;
+            for (int64_t v = 0; v < s.config().num_nodes; ++v) r.max_list_len = std::max<int64_t>(r.max_list_len, s.num_blocks(s.node_index(i, v)));
+        }
+        const int64_t n_nodes = (int64_t)(i1 - i0) * s.config().num_nodes;
+        r.avg_list_len = n_nodes ? (double)r.num_blocks / (double)n_nodes : 0.0;
+        // of a node's line 96 bytes are edge slots and 32 the node entry; extension and block lines are shared
+        // by all instances and counted in full
+        r.edge_data_bytes = (s.lines.size() - s.total_nodes()) * (int64_t)sizeof(tns::StoreLine) + n_nodes * (int64_t)(tns::kInlineSlots * sizeof(tns::Edge));
+        r.metadata_bytes = n_nodes * (int64_t)sizeof(tns::PrefixNodeHdr) + s.dir.size() * (int64_t)(sizeof(tns::BlockRec) + sizeof(uint32_t));
+        *out = r;
+        return TNS_OK;
+    }
     const tns::Store& s = *plan->store;
     for (int32_t i = i0; i < i1; ++i) {
         const tns::InstanceTotals& t = s.totals(i);
@@ -869,6 +931,15 @@ int64_t tns_node_blocks(const tns_plan* plan, int32_t instance, int32_t node, in
         }
         return n;
     }
+    if (plan->pstore) {
+        const tns::PrefixStore& s = *plan->pstore;
+        const int64_t nidx = s.node_index(instance, node);
+        const int64_t n = s.num_blocks(nidx);
+        for (int64_t i = 0; i < n && i < max_blocks; ++i)
+            s.block_info(nidx, (int32_t)i, cap ? cap + i : nullptr, size ? size + i : nullptr, t_min ? t_min + i : nullptr,
+                         t_max ? t_max + i : nullptr);
+        return n;
+    }
     const tns::Store& s = *plan->store;
     const int64_t nidx = s.node_index(instance, node);
     const int64_t n = s.nodes[nidx].nblocks;
@@ -885,8 +956,9 @@ int64_t tns_node_blocks(const tns_plan* plan, int32_t instance, int32_t node, in
 int tns_destroy(tns_plan* plan) {
     g_err.clear();
     if (!plan) return TNS_OK;
-    if (plan->d_nodes.ptr || plan->d_dir.ptr || plan->d_edges.ptr) {
+    if (plan->d_nodes.ptr || plan->d_dir.ptr || plan->d_edges.ptr || plan->d_lines.ptr) {
         DeviceGuard guard(plan->cfg.device);
+        plan->d_lines.release();
         plan->d_nodes.release();
         plan->d_dir.release();
         plan->d_dir_cum.release();

@@ -51,6 +51,9 @@ struct SampleArgs {
     int32_t wide_offsets;  // edge array has 2^31 or more entries: 64-bit positions in LDS
     int32_t first_ticket;  // 0; tests of the chained scan's bounded wait pass 1: tile 0 then never exists
     int32_t scan_ready;    // scan_ws is already cleared (multi-hop: one clearing launch for all hops)
+    int32_t prefix_layout; // the store is in the prefix layout: `edges` is the one array of lines, node v's line is line v
+    int32_t prefix_waves;  // prefix layout: waves per workgroup (0: default)
+    int32_t exp;                       // experiment switches (0: none)
     uint32_t* err_flag;    // where a chained scan whose bounded wait ran out reports it (null: the error word of scan_ws)
 };
 
@@ -76,6 +79,10 @@ size_t compact_workspace_bytes(int64_t Q);
 
 // Both only enqueue kernels on `stream`; they return the first launch error.
 hipError_t launch_sample(const SampleArgs& a, hipStream_t stream);
+// The same for a store in the prefix layout (tns_kernels_prefix.hip); launch_sample forwards to it.
+hipError_t launch_sample_prefix(const SampleArgs& a, hipStream_t stream);
+// Clears the chained scan's state for `num_tiles` tiles before a fused launch (kernel, capturable).
+hipError_t launch_scan_init(const SampleArgs& a, int64_t num_tiles, hipStream_t stream);
 hipError_t launch_compact(const CompactArgs& a, hipStream_t stream);
 // Clears `bytes` (a multiple of 8) of chained-scan workspace with a kernel (capturable, unlike a memset).
 hipError_t launch_scan_clear(void* ws, size_t bytes, hipStream_t stream);

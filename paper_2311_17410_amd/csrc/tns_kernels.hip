@@ -17,105 +17,13 @@
 //   * with the dense outputs requested, the workgroups pass their dense offsets along a chain
 //     (single-pass scan over tiles) and write the dense rows from registers.
 #include "tns_kernels.h"
+#include "tns_device.h"
 
 #include <algorithm>
 #include <type_traits>
 
 namespace tns {
 namespace {
-
-constexpr int kWave = 64;
-constexpr int kXcds = 8;
-
-// Workgroup -> tile mapping that gives each XCD (own L2) one contiguous range of tiles; the
-// hardware hands consecutive workgroup ids to the XCDs round-robin.
-__device__ __forceinline__ int64_t xcd_tile(int64_t bid, int64_t nb) {
-    const int64_t q = nb / kXcds, r = nb % kXcds;
-    const int64_t xcd = bid % kXcds, idx = bid / kXcds;
-    return xcd * q + (xcd < r ? xcd : r) + idx;
-}
-
-__device__ __forceinline__ uint32_t div_by(uint32_t s, uint32_t f, uint32_t magic) {
-    // floor(s / f) for s < 2^16 with magic = ceil(2^32 / f) (f >= 2)
-    return f == 1 ? s : __umulhi(s, magic);
-}
-
-// Rank in [0, c) for slot j of query qid: splitmix64 output function on the counter
-// seed + G * (qid * f + j + 1), top 32 bits scaled by multiply-shift.
-__device__ __forceinline__ uint64_t pick_rank(uint64_t seed, int64_t qid, int32_t f, int32_t j, uint64_t c) {
-    uint64_t z = seed + 0x9E3779B97F4A7C15ull * ((uint64_t)qid * (uint64_t)f + (uint64_t)j + 1ull);
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-    z ^= z >> 31;
-    return ((z >> 32) * c) >> 32;
-}
-
-__device__ __forceinline__ int32_t wave_inclusive_scan(int32_t v, int lane) {
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const int32_t u = __shfl_up(v, d, kWave);
-        if (lane >= d) v += u;
-    }
-    return v;
-}
-
-// ---- single-pass chained scan over workgroup tiles (padding removal fused into sampling) ----
-//
-// Workspace layout: word 0 = tile ticket, word 1 = error flag, then one 64-bit status per tile:
-// bits 62-63 = state (0 not ready, 1 tile total, 2 inclusive prefix), bits 0-61 = value.
-// Tiles take their index from the ticket, so a tile only ever waits for tiles that have
-// already started; the wait is bounded and sets the error flag if the bound is ever hit.
-constexpr uint64_t kStTotal = 1ull << 62, kStPrefix = 2ull << 62, kStMask = 3ull << 62;
-constexpr int kSpinLimit = 1 << 22;
-constexpr int kCoopGroup = 16;        // lanes per query in the cooperative search (recent policy, fan-out <= 16)
-constexpr int kGatherChunk = 10;      // gather iterations whose loads are issued together (8 and 5 measured slower)
-
-struct ScanWorkspace {
-    uint32_t ticket;
-    uint32_t error;
-    uint32_t pad[62];
-    uint64_t status[1];   // [number of tiles]
-};
-
-// Sum of the totals of all tiles before `tile` (called by one whole wave).
-__device__ __forceinline__ int64_t lookback_exclusive(ScanWorkspace* ws, uint32_t* err_flag, int64_t tile, int lane) {
-    int64_t excl = 0;
-    int64_t idx = tile - 1;
-    int spins = 0;
-    bool fresh = true;              // new window: every lane reads its tile's state
-    uint64_t st = 0;
-    while (true) {
-        const int64_t t = idx - lane;
-        // a lane re-reads only while its tile is not ready
-        if (fresh || (st & kStMask) == 0) {
-            st = kStPrefix;         // before the first tile: prefix 0
-            if (t >= 0) st = __hip_atomic_load(&ws->status[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        fresh = false;
-        const uint64_t state = st & kStMask;
-        const uint64_t is_prefix = __ballot(state == kStPrefix);
-        const uint64_t not_ready = __ballot(state == 0);
-        const int first = is_prefix ? __builtin_ctzll(is_prefix) : kWave;             // nearest tile with a full prefix
-        const uint64_t needed = first >= kWave - 1 ? ~0ull : ((2ull << first) - 1);    // lanes 0..first
-        if (not_ready & needed) {
-            if (++spins > kSpinLimit) {
-                // reported before this tile publishes anything, so that whoever builds on its (wrong)
-                // prefix can see the flag
-                if (lane == 0) atomicExch(err_flag, 1u);
-                __threadfence();
-                return excl;
-            }
-            __builtin_amdgcn_s_sleep(16);      // ~0.4 us between polls: late tiles are late by microseconds
-            continue;
-        }
-        int64_t v = (lane <= first) ? (int64_t)(st & ~kStMask) : 0;
-        for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, kWave);
-        excl += v;
-        if (first < kWave) return excl;
-        idx -= kWave;
-        fresh = true;
-    }
-}
 
 // Clears the ticket, the error flag and the tile states before a fused launch (a kernel rather
 // than a memset, so that the launch sequence can be captured into a graph).
@@ -137,241 +45,6 @@ __global__ void __launch_bounds__(256) tns_scan_init(ScanWorkspace* ws, int64_t 
 __global__ void __launch_bounds__(256) tns_scan_clear(uint64_t* ws, int64_t words) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i < words) ws[i] = 0;
-}
-
-// Unsigned index type of the same width as the LDS position entries: with a 32-bit index the edge
-// load is addressed as base + 32-bit offset, one register per address.
-template <typename pos_t> struct index_of { using type = uint64_t; };
-template <> struct index_of<int32_t> { using type = uint32_t; };
-
-// State of one lane's walk over the blocks of its target node, newest block first
-// (Algorithm 1).  `t` numbers the blocks in visiting order.
-template <int POLICY, bool INCL, typename pos_t>
-struct Walk {
-    float tb, te;                 // window [tb, te) or [tb, te]
-    int32_t f;
-    pos_t* s_pos;                 // this lane's f slots in LDS: word index of each selected edge
-    const uint32_t* __restrict__ edges;   // edge lines as 4-byte words
-    int32_t k = 0;                // slots filled so far (newest candidates first)
-    int64_t c = 0;                // uniform: candidates seen in all overlapping blocks
-    int32_t t_first = -1, t_last = -1, hi_first = 0, lo_last = 0;   // uniform: first/last overlapping block
-    int32_t n_blocks = 0, n_probes = 0;                              // counted for the byte model
-    // recent: search left to the wave.  When the window end falls inside a block, the lane only
-    // narrows the search to at most `group` slots [d_lo, d_lo + d_n) of that block (edges before
-    // d_lo are known to qualify); the wave then reads those timestamps side by side and counts,
-    // right before it gathers from the same lines.
-    int32_t group = 0;            // 0: the lane does every search itself
-    int64_t d_off = -1;           // slot index of that block's first edge, -1: nothing left to the wave
-    int32_t d_lo = 0, d_n = 0;
-
-    // first index i in [0, n) with ts[i] >= x (STRICT=false) or ts[i] > x (STRICT=true)
-    template <bool STRICT>
-    __device__ __forceinline__ int32_t first_not_before(int64_t off, int32_t n, float x) {
-        int32_t lo = 0, hi = n;
-        while (lo < hi) {
-            const int32_t mid = lo + ((hi - lo) >> 1);
-            const float t = __uint_as_float(edges[slot_word(off + mid)]);   // Edge::ts is the first word
-            ++n_probes;
-            const bool ge = STRICT ? (t > x) : (t >= x);
-            if (ge) hi = mid; else lo = mid + 1;
-        }
-        return lo;
-    }
-
-    // Examine one block; returns false when no older block can contribute.
-    __device__ __forceinline__ bool step(const BlockRec& r, int32_t t) {
-        ++n_blocks;
-        if (INCL ? (te < r.t_min) : (te <= r.t_min)) return true;   // block lies after the window: next older
-        if (tb > r.t_max) return false;                             // block lies before the window: stop
-        const int32_t size = rec_size(r);
-        const int64_t off = rec_off(r);
-        // candidate range [lo, hi) of the block; t_min / t_max settle most cases without a search
-        int32_t hi = size;
-        const bool all_before_end = INCL ? (te >= r.t_max) : (te > r.t_max);
-        const bool tomb = rec_tombstones(r);   // some edges of the block are deleted: they count as absent
-        if (POLICY == 0 && group > 0 && !tomb && !all_before_end && !(tb > r.t_min)) {
-            // only the newest overlapping block can contain the window end, so nothing is recorded yet
-            int32_t lo = 0;
-            while (hi - lo > group) {
-                const int32_t mid = lo + ((hi - lo) >> 1);
-                const float tm = __uint_as_float(edges[slot_word(off + mid)]);
-                ++n_probes;
-                const bool ge = INCL ? (tm > te) : (tm >= te);
-                if (ge) hi = mid; else lo = mid + 1;
-            }
-            d_off = off; d_lo = lo; d_n = hi - lo;
-            n_probes += d_n;
-            return true;            // older blocks supply the remaining slots
-        }
-        if (!all_before_end) hi = first_not_before<INCL>(off, size, te);
-        int32_t lo = 0;
-        if (tb > r.t_min) lo = first_not_before<false>(off, hi, tb);
-        int32_t cnt = hi - lo;
-        if (tomb) {
-            // slow path: look at every candidate's validity (the edge id word), newest first
-            cnt = 0;
-            for (int32_t i = hi - 1; i >= lo; --i) {
-                const int32_t id = (int32_t)edges[slot_word(off + i) + 2];
-                ++n_probes;
-                if (id < 0) continue;
-                if (k < f) s_pos[k++] = (pos_t)slot_word(off + i);
-                ++cnt;
-                if (POLICY == 0 && k >= f) break;
-            }
-            if (POLICY == 1 && cnt > 0) {
-                if (t_first < 0) { t_first = t; hi_first = hi; }
-                t_last = t; lo_last = lo;
-                c += cnt;
-            }
-        } else if (cnt > 0) {
-            const int32_t take = min(f - k, cnt);
-            for (int32_t j = 0; j < take; ++j) s_pos[k + j] = (pos_t)slot_word(off + hi - 1 - j);
-            k += take > 0 ? take : 0;
-            if (POLICY == 1) {
-                if (t_first < 0) { t_first = t; hi_first = hi; }
-                t_last = t; lo_last = lo;
-                c += cnt;
-            }
-        }
-        if (lo > 0) return false;                  // everything older is before the window
-        if (POLICY == 0 && k >= f) return false;   // recent: the newest f are found
-        return true;
-    }
-
-    // Uniform with more candidates than slots: f independent picks, rank counted from the
-    // oldest candidate, stored as the negated distance from the newest one until resolved.
-    __device__ __forceinline__ void draw(uint64_t seed, int64_t qid) {
-        for (int32_t j = 0; j < f; ++j) {
-            const int64_t from_newest = c - 1 - (int64_t)pick_rank(seed, qid, f, j, (uint64_t)c);
-            s_pos[j] = (pos_t)(-(from_newest + 1));
-        }
-    }
-
-    // Second visit of an overlapping block: turn the ranks that fall into it into positions.
-    __device__ __forceinline__ void resolve(const BlockRec& r, int32_t t, int64_t& cum) {
-        ++n_blocks;
-        const int32_t hi = (t == t_first) ? hi_first : rec_size(r);
-        const int32_t lo = (t == t_last) ? lo_last : 0;
-        int64_t cnt = hi - lo;
-        const int64_t off = rec_off(r);
-        if (rec_tombstones(r)) {
-            // ranks count valid edges only: walk them newest first
-            cnt = 0;
-            for (int32_t i = hi - 1; i >= lo; --i) {
-                if ((int32_t)edges[slot_word(off + i) + 2] < 0) continue;
-                for (int32_t j = 0; j < f; ++j) {
-                    const int64_t sv = (int64_t)s_pos[j];
-                    if (sv < 0 && -(sv + 1) - cum == cnt) s_pos[j] = (pos_t)slot_word(off + i);
-                }
-                ++cnt;
-            }
-        } else {
-            for (int32_t j = 0; j < f; ++j) {
-                const int64_t sv = (int64_t)s_pos[j];
-                if (sv < 0) {
-                    const int64_t rr = -(sv + 1) - cum;
-                    if (rr < cnt) s_pos[j] = (pos_t)slot_word(off + hi - 1 - rr);
-                }
-            }
-        }
-        cum += cnt;
-    }
-};
-
-// Ordering between LDS writes and reads of the SAME wave (rows are wave-private): the hardware
-// executes a wave's LDS operations in order, so only the compiler must not reorder them.
-__device__ __forceinline__ void wave_lds_sync() {
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-}
-
-__device__ __forceinline__ int64_t shfl64(int64_t v, int src) {
-    const int lo = __shfl((int)(uint32_t)(v & 0xffffffffll), src, kWave);
-    const int hi = __shfl((int)(v >> 32), src, kWave);
-    return ((int64_t)hi << 32) | (uint32_t)lo;
-}
-
-// Word index of the edge in slot j of a query: the first hq slots come from the block whose
-// search the wave finished (newest first), the others from the positions the lane recorded.
-// The wave's cooperative gather: its 64*f slots in flat order, lane l handles slot it*64 + l, so
-// consecutive lanes read consecutive edges of one query (12-byte loads within one or two lines)
-// and every store instruction covers 256 consecutive bytes of an output array.  The loads of up to
-// kGatherChunk iterations are issued together, into registers, before anything is stored: the
-// wave pays the memory latency once per batch instead of once per slot.
-struct GatherRegs {
-    int32_t nbr[kGatherChunk], eid[kGatherChunk];     // eid < 0: empty slot (edge ids are non-negative)
-    float ts[kGatherChunk];
-};
-
-template <typename pos_t>
-__device__ __forceinline__ void gather_load(GatherRegs& g, const SampleArgs& p, uint32_t f_magic, int32_t stride,
-                                            const pos_t* __restrict__ w_pos, int lane, int32_t it0, int32_t k) {
-    const int32_t f = p.fanout;
-#pragma unroll
-    for (int i = 0; i < kGatherChunk; ++i) {
-        g.nbr[i] = -1; g.eid[i] = -1; g.ts[i] = 0.0f;
-        if (it0 + i < f) {
-            const uint32_t s = (uint32_t)((it0 + i) * kWave + lane);
-            const uint32_t ql = div_by(s, (uint32_t)f, f_magic);
-            const int32_t j = (int32_t)(s - ql * (uint32_t)f);
-            const int32_t kq = __shfl(k, (int)ql, kWave);
-            if (j < kq) {
-                const auto pos = (typename index_of<pos_t>::type)w_pos[ql * stride + j];
-                const Edge e = *reinterpret_cast<const Edge*>(p.edges + pos);
-                g.nbr[i] = e.nbr; g.eid[i] = e.eid; g.ts[i] = e.ts;
-            }
-        }
-    }
-}
-
-// padded rows: slots of queries below Q, empty slots get the sentinels
-__device__ __forceinline__ void store_padded(const GatherRegs& g, const SampleArgs& p, uint32_t f_magic, int lane,
-                                             int32_t it0, int64_t q0, int64_t Q) {
-    const int32_t f = p.fanout;
-    const int64_t out0 = q0 * f;
-#pragma unroll
-    for (int i = 0; i < kGatherChunk; ++i) {
-        if (it0 + i < f) {
-            const uint32_t s = (uint32_t)((it0 + i) * kWave + lane);
-            const uint32_t ql = div_by(s, (uint32_t)f, f_magic);
-            if (q0 + (int64_t)ql < Q) {
-                __builtin_nontemporal_store(g.nbr[i], &p.out_nbr[out0 + s]);
-                __builtin_nontemporal_store(g.eid[i], &p.out_eid[out0 + s]);
-                __builtin_nontemporal_store(g.ts[i], &p.out_ts[out0 + s]);
-            }
-        }
-    }
-}
-
-// dense copy: `row` = where the lane's own query starts; consecutive lanes write consecutive entries
-__device__ __forceinline__ void store_dense(const GatherRegs& g, const SampleArgs& p, uint32_t f_magic, int lane,
-                                            int32_t it0, int64_t row) {
-    const int32_t f = p.fanout;
-#pragma unroll
-    for (int i = 0; i < kGatherChunk; ++i) {
-        if (it0 + i < f) {
-            const uint32_t s = (uint32_t)((it0 + i) * kWave + lane);
-            const uint32_t ql = div_by(s, (uint32_t)f, f_magic);
-            const int32_t j = (int32_t)(s - ql * (uint32_t)f);
-            const int64_t rowq = shfl64(row, (int)ql);
-            if (g.eid[i] >= 0) {
-                p.cmp_nbr[rowq + j] = g.nbr[i];
-                p.cmp_eid[rowq + j] = g.eid[i];
-                p.cmp_ts[rowq + j] = g.ts[i];
-            }
-        }
-    }
-}
-
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ BlockRec as_rec(const uint4& u) {
-    BlockRec r;
-    r.t_min = __uint_as_float(u.x);
-    r.t_max = __uint_as_float(u.y);
-    r.off_lo = u.z;
-    r.size_hi = u.w;
-    return r;
 }
 
 // FUSED: also removes the padding in the same pass (rowptr and dense arrays), with the tile
@@ -686,21 +359,23 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256, FUSED ? 4 : 6) tns_sample_
             int is_last = 0;
             if (lane == kWave - 1) {
                 s_wave_sum[wave] = inc;
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
                 is_last = __hip_atomic_fetch_add(&s_arrived, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) == waves_per_wg - 1;
             }
             is_last = __shfl(is_last, kWave - 1, kWave);
             int32_t wg_total = 0;
             if (is_last) {
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
                 for (int i = 0; i < waves_per_wg; ++i) wg_total += s_wave_sum[i];
                 publish_total(wg_total);
             }
             wave_lds_sync();      // the positions were written by this wave's own lanes
             gather_load(g, p, f_magic, stride, w_pos, lane, 0, k);
-            store_padded(g, p, f_magic, lane, 0, q0, Q);
+            // The look-back reads come before this wave's stores: a load result can only be waited for
+            // together with every store issued before it, and a store takes microseconds to be taken.
             if (is_last) chain(wg_total);
-            __syncthreads();
+            store_padded(g, p, f_magic, lane, 0, q0, Q);
+            lds_barrier();
             const int64_t row = s_tile_base + offset_of_wave() + (inc - k);
             write_rowptr(row);
             store_dense(g, p, f_magic, lane, 0, row);
@@ -878,9 +553,8 @@ hipError_t launch_sample_t(const SampleArgs& a, hipStream_t stream) {
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     if (FUSED && !a.scan_ready) {
         // one state more than tiles: the workspace has it, and a test that starts the tickets at 1 uses it
-        const unsigned init_grid = (unsigned)std::max<int64_t>(1, (grid + 1 + 255) / 256);
-        hipLaunchKernelGGL(tns_scan_init, dim3(init_grid), dim3(256), 0, stream, static_cast<ScanWorkspace*>(a.scan_ws),
-                           grid + 1, a.rowptr, a.Q, a.Q_dev, a.total_out, (uint32_t)a.first_ticket);
+        const hipError_t e = launch_scan_init(a, grid + 1, stream);
+        if (e != hipSuccess) return e;
     }
     if (grid <= 0) return hipGetLastError();
     const size_t lds = chunk * waves;
@@ -903,7 +577,15 @@ size_t compact_workspace_bytes(int64_t Q) {
     return std::max(sums + offs + 256, (fused + 255) & ~size_t(255));
 }
 
+hipError_t launch_scan_init(const SampleArgs& a, int64_t num_tiles, hipStream_t stream) {
+    const unsigned init_grid = (unsigned)std::max<int64_t>(1, (num_tiles + 255) / 256);
+    hipLaunchKernelGGL(tns_scan_init, dim3(init_grid), dim3(256), 0, stream, static_cast<ScanWorkspace*>(a.scan_ws), num_tiles,
+                       a.rowptr, a.Q, a.Q_dev, a.total_out, (uint32_t)a.first_ticket);
+    return hipGetLastError();
+}
+
 hipError_t launch_sample(const SampleArgs& a, hipStream_t stream) {
+    if (a.prefix_layout) return launch_sample_prefix(a, stream);
     const bool incl = a.inclusive_end != 0;
     const bool wide = a.wide_offsets != 0;
 #define TNS_DISPATCH(POL, CNT, FUS)                                                          \

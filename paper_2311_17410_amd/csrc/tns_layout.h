@@ -1,7 +1,7 @@
 // Record layouts shared by the host-side store builder and the device kernels.
 //
 // The paper (section 4.1) lists what a node entry and an edge block hold but not their byte
-// layout ("lightweight structures (72 bytes)") and links a node's blocks into a doubly-linked
+// layout (it only gives the size of a block's metadata) and links a node's blocks into a doubly-linked
 // list.  On MI355X every dependent random read costs a 128-byte line from HBM, so a linked
 // list of separately allocated records costs one line per block visited.  Here the records of
 // one node sit next to each other instead:
@@ -90,5 +90,57 @@ TNS_HD int64_t slot_word(int64_t s) {
     const int64_t line = s / kSlotsPerLine;
     return line * 32 + (s - line * kSlotsPerLine) * 3;
 }
+
+// ---- prefix layout (TNS_FLAG_PREFIX_LAYOUT) ------------------------------------------------------
+//
+// A second placement of the same logical structure (node table, chronological block lists, block
+// capacities by the sizing rule of section 4.1), made to cut the number of 128-byte lines a query
+// touches.  Node table and edge data share ONE array of 128-byte lines of 10 slot positions each, so
+// that every edge is addressed by one slot index whatever line it lives in:
+//
+//   * line v (v < number of nodes) is node v's line: slot positions 0..7 hold the node's first eight
+//     edge slots, the last 32 bytes (slot positions 8, 9 and the line's spare 8 bytes) the node entry;
+//   * a node's first blocks are carved, in order, out of its "prefix": 38 consecutive slots = the 8
+//     slots in its own line plus up to three extension lines of 10 (allocated when a block reaches
+//     into them, never moved).  A block belongs to the prefix while the capacities so far fit; the
+//     first block that does not fit, and every later one, is placed on its own as in the default
+//     layout and gets a 16-byte record in the node's run of the directory pool;
+//   * inside the prefix, blocks are contiguous and all but the newest are full, so edge i of the node
+//     sits in prefix slot i: the time index over the prefix is one fence per extension line (the
+//     timestamp of its first slot), kept in the node entry.  Block capacities of prefix blocks are
+//     needed by insertion and inspection only and stay on the host.
+constexpr int kInlineSlots = 8;                                    // edge slots in the node's own line
+constexpr int kPrefixExtLines = 3;                                 // extension lines of the prefix
+constexpr int kPrefixSlots = kInlineSlots + kPrefixExtLines * kSlotsPerLine;   // 38
+
+// Node entry = words 24..31 of the node's line.
+constexpr int kNodeHdrWord = 24;
+struct PrefixNodeHdr {
+    int32_t degree;      // stored edges
+    uint32_t meta;       // bit 0: node deleted; bit 1: node holds deleted edges; bits 2-3: extension lines that
+                         // hold edges; bits 4-9: slots of the prefix given to blocks; bits 10-31: blocks outside the prefix
+    uint32_t ext0;       // line index of the first extension line
+    uint32_t ext12;      // line index of the second extension line; the third follows it
+    float fence[kPrefixExtLines];   // timestamp of the first slot of each extension line
+    uint32_t dir_line;   // blocks outside the prefix: start of the node's record run, in units of kDirAlign records
+};
+static_assert(sizeof(PrefixNodeHdr) == 32, "node entry is 32 bytes");
+TNS_HD int32_t pmeta_ext_lines(uint32_t m) { return (int32_t)((m >> 2) & 3u); }
+TNS_HD int32_t pmeta_prefix_slots(uint32_t m) { return (int32_t)((m >> 4) & 63u); }
+TNS_HD int32_t pmeta_big_blocks(uint32_t m) { return (int32_t)(m >> 10); }
+TNS_HD uint32_t make_pmeta(uint32_t flags, int32_t ext_lines, int32_t prefix_slots, int32_t big_blocks) {
+    return (flags & 3u) | ((uint32_t)ext_lines << 2) | ((uint32_t)prefix_slots << 4) | ((uint32_t)big_blocks << 10);
+}
+constexpr int32_t kMaxBigBlocks = (1 << 22) - 1;
+// A line of the prefix layout's array, seen as edge data or as a node's line.
+struct alignas(128) PrefixNodeLine {
+    Edge e[kInlineSlots];
+    PrefixNodeHdr hdr;
+};
+union alignas(128) StoreLine {
+    EdgeLine edges;
+    PrefixNodeLine node;
+};
+static_assert(sizeof(StoreLine) == 128, "a line is 128 bytes");
 
 }  // namespace tns

@@ -161,8 +161,6 @@ void Store::set_node_deleted(int32_t inst, int32_t v, bool deleted) {
     nd.flags = deleted ? (nd.flags | 1) : (nd.flags & ~1);
 }
 
-namespace {
-
 // Stable LSD radix sort of batch positions by source node id (11 bits per pass).
 void group_by_source(const int32_t* src, int64_t m, int64_t num_nodes, std::vector<uint32_t>& ord,
                      std::vector<uint32_t>& tmp) {
@@ -184,8 +182,6 @@ void group_by_source(const int32_t* src, int64_t m, int64_t num_nodes, std::vect
         ord.swap(tmp);
     }
 }
-
-}  // namespace
 
 int Store::add_edges(int32_t inst, const int32_t* src, const int32_t* dst, const float* ts, const int32_t* eid,
                      int64_t m, std::string& err) {

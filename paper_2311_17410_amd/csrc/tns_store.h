@@ -151,4 +151,8 @@ private:
     std::vector<uint32_t> ord_, tmp_;     // scratch: batch positions grouped by source node
 };
 
+// Stable grouping of batch positions by source node id (shared by the two builders).
+void group_by_source(const int32_t* src, int64_t m, int64_t num_nodes, std::vector<uint32_t>& ord,
+                     std::vector<uint32_t>& tmp);
+
 }  // namespace tns

@@ -2,8 +2,19 @@
 the CPU oracle and compare every output array bit for bit."""
 import numpy as np
 
+LAYOUT_FLAGS = 0          # set by the `layout` fixture (conftest.py): flag of the store layout under test
+
+
+def with_layout(B, flags):
+    """`flags` plus the flag of the layout under test; skips the test if the two cannot be combined."""
+    if LAYOUT_FLAGS and flags & (B.TNS_FLAG_EDGES_ON_HOST | B.TNS_FLAG_ALL_ON_HOST | B.TNS_FLAG_DEVICE_INGEST | B.TNS_FLAG_NO_NODE_SLAB):
+        import pytest
+        pytest.skip("this plan's flags exclude the prefix layout")
+    return flags | LAYOUT_FLAGS
+
 
 def build_plan(B, wl, policy=0, inclusive_end=0, seed=0, fanout=None, tau=None, sizing=0, batch=None, flags=0):
+    flags = with_layout(B, flags)
     plan = B.Plan(wl.num_nodes, fanout or wl.fanout, policy=policy, block_threshold=tau or wl.tau,
                   num_instances=wl.num_instances, sizing=sizing, inclusive_end=inclusive_end, seed=seed, flags=flags)
     for i, st in enumerate(wl.streams):

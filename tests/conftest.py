@@ -35,3 +35,13 @@ def oracle_lib():
     import oracle
     oracle.build()
     return oracle
+
+
+@pytest.fixture(params=[0, 128], ids=["blocks", "prefix"])
+def layout(request):
+    """Runs a GPU test once per store layout: the plans that tests/_harness.build_plan creates get the
+    layout's flag (TNS_FLAG_PREFIX_LAYOUT = 128); a test whose plan cannot take it is skipped for it."""
+    import _harness
+    _harness.LAYOUT_FLAGS = request.param
+    yield request.param
+    _harness.LAYOUT_FLAGS = 0

@@ -41,7 +41,9 @@ def test_argument_validation():
                        (dict(num_nodes=4, fanout=3, num_instances=0), B.TNS_EINVAL),
                        (dict(num_nodes=4, fanout=3, sizing=3), B.TNS_EINVAL),
                        (dict(num_nodes=4, fanout=3, inclusive_end=2), B.TNS_EINVAL),
-                       (dict(num_nodes=4, fanout=3, flags=128), B.TNS_EINVAL),
+                       (dict(num_nodes=4, fanout=3, flags=256), B.TNS_EINVAL),
+                       (dict(num_nodes=4, fanout=3, flags=B.TNS_FLAG_PREFIX_LAYOUT | B.TNS_FLAG_DEVICE_INGEST), B.TNS_EINVAL),
+                       (dict(num_nodes=4, fanout=3, flags=B.TNS_FLAG_PREFIX_LAYOUT | B.TNS_FLAG_EDGES_ON_HOST), B.TNS_EINVAL),
                        (dict(num_nodes=4, fanout=3, flags=B.TNS_FLAG_DEVICE_INGEST | B.TNS_FLAG_EDGES_ON_HOST), B.TNS_EINVAL),
                        (dict(num_nodes=4, fanout=3, flags=B.TNS_FLAG_DEVICE_INGEST | B.TNS_FLAG_NO_NODE_SLAB), B.TNS_EINVAL),
                        (dict(num_nodes=4, fanout=3, flags=B.TNS_FLAG_EDGES_ON_HOST | B.TNS_FLAG_ALL_ON_HOST), B.TNS_EINVAL)]:
@@ -81,8 +83,12 @@ def test_argument_validation():
     assert B.lib().tns_strerror(-2).decode().startswith("edges out of")
 
 
-def test_out_of_order_batch_rejected_and_store_unchanged():
-    h = B.tns_plan_create(num_nodes=2, fanout=3, block_threshold=4)
+LAYOUTS = [0, B.TNS_FLAG_PREFIX_LAYOUT]
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_out_of_order_batch_rejected_and_store_unchanged(layout):
+    h = B.tns_plan_create(num_nodes=2, fanout=3, block_threshold=4, flags=layout)
     B.tns_add_edges(h, 0, [0, 0], [1, 1], [1.0, 5.0])
     with pytest.raises(B.TnsError) as ei:
         B.tns_add_edges(h, 0, [1, 0], [0, 0], [6.0, 4.0])
@@ -120,11 +126,37 @@ def test_sizing_closed_forms():
     B.tns_destroy(h)
 
 
+def test_prefix_layout_closed_forms():
+    # same block lists as the default layout; the first blocks (1, 1, 2, 4, 8, 16 = 32 slots) are carved out
+    # of the node's prefix (own line + three extension lines), the later ones get records in a directory run
+    h = B.tns_plan_create(num_nodes=1, fanout=3, block_threshold=16, flags=B.TNS_FLAG_PREFIX_LAYOUT)
+    for i in range(100):
+        B.tns_add_edges(h, 0, [0], [i], [float(i)])
+    blk = B.tns_node_blocks(h, 0, 0)
+    caps = list(blk["cap"])
+    assert caps[:6] == [1, 1, 2, 4, 8, 16] and set(caps[6:]) == {16} and len(caps) == 11
+    assert list(blk["t_min"][:7]) == [0.0, 1.0, 2.0, 4.0, 8.0, 16.0, 32.0] and blk["t_max"][-1] == 99.0
+    assert list(blk["size"]) == [1, 1, 2, 4, 8, 16, 16, 16, 16, 16, 4]
+    st = B.tns_stats(h)
+    # node entry 32 B + one run of 8 records for the five blocks outside the prefix; edge data: 96 B in the
+    # node's line, 3 extension lines, 5 blocks of 16 slots in 2 lines each
+    assert st["metadata_bytes"] == 32 + 8 * (16 + 4) and st["edge_data_bytes"] == 96 + (3 + 10) * 128
+    assert st["wasted_slots"] == 12 and st["num_blocks"] == 11 and st["max_list_len"] == 11
+    B.tns_destroy(h)
+    # a first batch larger than the prefix: no prefix block at all
+    h = B.tns_plan_create(num_nodes=2, fanout=3, block_threshold=8, flags=B.TNS_FLAG_PREFIX_LAYOUT)
+    B.tns_add_edges(h, 0, [1] * 50, [0] * 50, np.arange(50))
+    B.tns_add_edges(h, 0, [1] * 3, [0] * 3, np.arange(50, 53))
+    assert list(B.tns_node_blocks(h, 0, 1)["cap"]) == [50, 8] and list(B.tns_node_blocks(h, 0, 1)["size"]) == [50, 3]
+    B.tns_destroy(h)
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("sizing", [0, 1, 2])
 @pytest.mark.parametrize("tau,batch", [(1, 64), (48, 128), (8192, 1 << 12), (16, 1 << 14)])
-def test_layout_matches_structural_oracle(oracle_lib, sizing, tau, batch):
+def test_layout_matches_structural_oracle(oracle_lib, sizing, tau, batch, layout):
     st = W.zipf_stream(np.random.Generator(np.random.PCG64(9)), 1 << 14, 1 << 9, batch, 1.1, "normal")
-    h = B.tns_plan_create(num_nodes=st.num_nodes, fanout=10, block_threshold=tau, sizing=sizing)
+    h = B.tns_plan_create(num_nodes=st.num_nodes, fanout=10, block_threshold=tau, sizing=sizing, flags=layout)
     for lo, hi in st.batches():
         B.tns_add_edges(h, 0, st.src[lo:hi], st.dst[lo:hi], st.ts[lo:hi])
     bs = oracle_lib.BlockStore(st.num_nodes, tau, sizing)
@@ -145,8 +177,9 @@ def test_layout_matches_structural_oracle(oracle_lib, sizing, tau, batch):
     B.tns_destroy(h)
 
 
-def test_instances_are_independent_in_the_builder():
-    h = B.tns_plan_create(num_nodes=3, fanout=2, block_threshold=4, num_instances=3)
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_instances_are_independent_in_the_builder(layout):
+    h = B.tns_plan_create(num_nodes=3, fanout=2, block_threshold=4, num_instances=3, flags=layout)
     B.tns_add_edges(h, 0, [0, 1], [1, 2], [5.0, 6.0])
     B.tns_add_edges(h, 2, [0, 0, 0], [1, 2, 1], [1.0, 2.0, 3.0])   # older times are fine in another instance
     assert B.tns_stats(h, 0)["num_edges"] == 2 and B.tns_stats(h, 1)["num_edges"] == 0
@@ -155,8 +188,9 @@ def test_instances_are_independent_in_the_builder():
     B.tns_destroy(h)
 
 
-def test_tombstone_deletion_on_the_host():
-    h = B.tns_plan_create(num_nodes=3, fanout=2, block_threshold=4)
+@pytest.mark.parametrize("layout", LAYOUTS)
+def test_tombstone_deletion_on_the_host(layout):
+    h = B.tns_plan_create(num_nodes=3, fanout=2, block_threshold=4, flags=layout)
     B.tns_add_edges(h, 0, [0, 0, 1, 0], [1, 2, 0, 1], [1.0, 2.0, 3.0, 4.0])
     with pytest.raises(B.TnsError) as ei:
         B.tns_add_edges(h, 0, [0], [1], [9.0], eid=[-5])             # ids must be non-negative

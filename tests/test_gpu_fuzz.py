@@ -36,14 +36,16 @@ def _case(seed):
 
 
 @pytest.mark.parametrize("seed", range(160))
-def test_random_configuration(B, oracle_lib, seed):
+def test_random_configuration(B, oracle_lib, seed, layout):
     import torch
     c = _case(seed)
+    if layout and c["device_built"]:
+        pytest.skip("the device builder writes the default layout")
     rng, n = c["rng"], c["n"]
     if c["batch"] == 1 and n > 600:          # one edge per batch: keep the number of ingestion calls small
         n = 600
         c["src"], c["dst"], c["ts"] = c["src"][:n], c["dst"][:n], c["ts"][:n]
-    flags = (B.TNS_FLAG_DEVICE_INGEST if c["device_built"] else 0) | (B.TNS_FLAG_WIDE_POSITIONS if c["wide"] else 0)
+    flags = (B.TNS_FLAG_DEVICE_INGEST if c["device_built"] else 0) | (B.TNS_FLAG_WIDE_POSITIONS if c["wide"] else 0) | layout
     plan = B.Plan(c["num_nodes"], c["f"], policy=c["policy"], block_threshold=c["tau"], sizing=c["sizing"],
                   inclusive_end=c["incl"], seed=c["seed"], flags=flags)
     bounds = list(range(0, n, c["batch"])) + [n]

@@ -5,10 +5,10 @@ import numpy as np
 import pytest
 
 from paper_2311_17410_amd import workloads as W
-from _harness import assert_same, build_plan, gpu_sample, oracle_sample
+from _harness import assert_same, build_plan, gpu_sample, oracle_sample, with_layout
 from conftest import progress
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("layout")]
 
 
 @pytest.fixture(scope="module")
@@ -117,7 +117,7 @@ def test_edge_cases(B, oracle_lib):
 def test_incremental_commit(B, oracle_lib):
     st = W.tiny_stream(61, 4000, 40, 500, ties=True)
     wl = wl_of(st, fanout=10, tau=16)
-    plan = B.Plan(st.num_nodes, 10, block_threshold=16)
+    plan = B.Plan(st.num_nodes, 10, block_threshold=16, flags=with_layout(B, 0))
     targets, t_start, t_end = W.random_queries(62, st, 777)
     for upto in (500, 1500, 4000):
         lo = 0 if upto == 500 else (500 if upto == 1500 else 1500)
@@ -396,7 +396,7 @@ def test_host_placement_gives_the_same_results(B, oracle_lib, policy):
     targets, t_start, t_end, _ = wl.queries(window_frac=0.25)
     ref = oracle_sample(oracle_lib, wl, targets, t_start, t_end, None, wl.fanout, policy, 0, 5, threads=16)
     for flags in (B.TNS_FLAG_EDGES_ON_HOST, B.TNS_FLAG_ALL_ON_HOST):
-        plan = B.Plan(wl.num_nodes, wl.fanout, policy=policy, block_threshold=wl.tau, seed=5, flags=flags)
+        plan = B.Plan(wl.num_nodes, wl.fanout, policy=policy, block_threshold=wl.tau, seed=5, flags=with_layout(B, flags))
         half = st.n // 2
         for lo, hi in ((0, half), (half, st.n)):
             for a in range(lo, hi, st.batch):

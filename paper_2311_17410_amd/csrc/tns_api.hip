@@ -552,10 +552,6 @@ static int fill_sample_args(tns_plan* plan, int64_t Q, const int32_t* d_targets,
         a.nodes = nullptr;
         a.edges = reinterpret_cast<const uint32_t*>(plan->d_lines.ptr);
         a.prefix_layout = 1;
-        static const int env_waves = [] { const char* v = std::getenv("TNS_PREFIX_WAVES"); return v ? std::atoi(v) : 0; }();
-        a.prefix_waves = env_waves;     // tuning aid: waves per workgroup of the prefix-layout kernel
-        static const int env_exp = [] { const char* v = std::getenv("TNS_EXP"); return v ? std::atoi(v) : 0; }();
-        a.exp = env_exp;
     }
     a.targets = d_targets;
     a.t_start = d_t_start;
@@ -612,7 +608,8 @@ static int run_impl(tns_plan* plan, int64_t Q, const int32_t* d_targets, const f
     DeviceGuard guard(plan->cfg.device);
     if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the plan's device");
     if (static_scratch && want_cmp) {
-        if (Q > kStaticMaxQueries) return fail(TNS_ESIZE, "tns_run_static serves at most 2^24 queries per call");
+        if (Q > kStaticMaxQueries || tns::compact_workspace_bytes(Q) > kStaticScratchBytes)
+            return fail(TNS_ESIZE, "tns_run_static serves at most 2^24 queries per call");
         if ((rc = static_scratch_of(plan->cfg.device, &d_workspace))) return rc;
         workspace_bytes = kStaticScratchBytes;
     }

@@ -64,6 +64,12 @@ struct ScanWorkspace {
     uint64_t status[1];   // [number of tiles]
 };
 
+__device__ __forceinline__ int64_t shfl64(int64_t v, int src) {
+    const int lo = __shfl((int)(uint32_t)(v & 0xffffffffll), src, kWave);
+    const int hi = __shfl((int)(v >> 32), src, kWave);
+    return ((int64_t)hi << 32) | (uint32_t)lo;
+}
+
 // Sum of the totals of all tiles before `tile` (called by one whole wave).
 __device__ __forceinline__ int64_t lookback_exclusive(ScanWorkspace* ws, uint32_t* err_flag, int64_t tile, int lane) {
     int64_t excl = 0;
@@ -103,6 +109,7 @@ __device__ __forceinline__ int64_t lookback_exclusive(ScanWorkspace* ws, uint32_
         fresh = true;
     }
 }
+
 
 // Unsigned index type of the same width as the LDS position entries: with a 32-bit index the edge
 // load is addressed as base + 32-bit offset, one register per address.
@@ -269,11 +276,6 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-__device__ __forceinline__ int64_t shfl64(int64_t v, int src) {
-    const int lo = __shfl((int)(uint32_t)(v & 0xffffffffll), src, kWave);
-    const int hi = __shfl((int)(v >> 32), src, kWave);
-    return ((int64_t)hi << 32) | (uint32_t)lo;
-}
 
 // Word index of the edge in slot j of a query: the first hq slots come from the block whose
 // search the wave finished (newest first), the others from the positions the lane recorded.
@@ -287,7 +289,9 @@ struct GatherRegs {
     float ts[kGatherChunk];
 };
 
-template <typename pos_t>
+// BRANCHY: each load sits in its own branch instead (uniform policy: every slot of a query lies in another
+// line and the variant below measured slower there, C5 step 35.4 against 31.2 ms).
+template <typename pos_t, bool BRANCHY = false>
 __device__ __forceinline__ void gather_load(GatherRegs& g, const SampleArgs& p, uint32_t f_magic, int32_t stride,
                                             const pos_t* __restrict__ w_pos, int lane, int32_t it0, int32_t k) {
     const int32_t f = p.fanout;
@@ -295,6 +299,24 @@ __device__ __forceinline__ void gather_load(GatherRegs& g, const SampleArgs& p, 
     // issued before the first result is looked at: loads inside divergent branches make the compiler lose
     // count of the memory operations in flight, and it then waits for ALL of them, stores included, before
     // every store that follows.
+    if (BRANCHY) {
+#pragma unroll
+        for (int i = 0; i < kGatherChunk; ++i) {
+            g.nbr[i] = -1; g.eid[i] = -1; g.ts[i] = 0.0f;
+            if (it0 + i < f) {
+                const uint32_t s = (uint32_t)((it0 + i) * kWave + lane);
+                const uint32_t ql = div_by(s, (uint32_t)f, f_magic);
+                const int32_t j = (int32_t)(s - ql * (uint32_t)f);
+                const int32_t kq = __shfl(k, (int)ql, kWave);
+                if (j < kq) {
+                    const auto pos = (typename index_of<pos_t>::type)w_pos[ql * stride + j];
+                    const Edge e = *reinterpret_cast<const Edge*>(p.edges + pos);
+                    g.nbr[i] = e.nbr; g.eid[i] = e.eid; g.ts[i] = e.ts;
+                }
+            }
+        }
+        return;
+    }
     bool filled[kGatherChunk];
     Edge raw[kGatherChunk];
 #pragma unroll

@@ -52,8 +52,6 @@ struct SampleArgs {
     int32_t first_ticket;  // 0; tests of the chained scan's bounded wait pass 1: tile 0 then never exists
     int32_t scan_ready;    // scan_ws is already cleared (multi-hop: one clearing launch for all hops)
     int32_t prefix_layout; // the store is in the prefix layout: `edges` is the one array of lines, node v's line is line v
-    int32_t prefix_waves;  // prefix layout: waves per workgroup (0: default)
-    int32_t exp;                       // experiment switches (0: none)
     uint32_t* err_flag;    // where a chained scan whose bounded wait ran out reports it (null: the error word of scan_ws)
 };
 

@@ -23,7 +23,6 @@
 // the prefix, then the prefix's lines as blocks of their own, the node's own line from registers.  They
 // leave edge positions in their row and the output stage loads those edges from memory.
 #include <algorithm>
-#include <cstdlib>
 
 #include "tns_device.h"
 #include "tns_kernels.h"
@@ -169,7 +168,7 @@ __device__ __forceinline__ void walked_gather(const SampleArgs& p, uint32_t f_ma
 }
 
 template <int POLICY, bool INCL, typename pos_t, bool COUNT, bool FUSED>
-__global__ void __launch_bounds__(256, 5) tns_sample_prefix_kernel(const SampleArgs p, const int32_t rs, const uint32_t f_magic,
+__global__ void __launch_bounds__(1024) tns_sample_prefix_kernel(const SampleArgs p, const int32_t rs, const uint32_t f_magic,
                                                                  const int32_t gshift, const uint32_t chunk,
                                                                  const uint32_t rows_bytes) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -294,7 +293,7 @@ __global__ void __launch_bounds__(256, 5) tns_sample_prefix_kernel(const SampleA
         for (int j = 0; j < kPrefixExtLines; ++j)
             if (j < n_ext && (INCL ? (fence(j) <= te) : (fence(j) < te))) e = j;
     }
-    const bool need1 = fast && e >= 0 && !(p.exp & 8);
+    const bool need1 = fast && e >= 0;
     const int32_t n_e = need1 ? min(fill - kInlineSlots - kSlotsPerLine * e, kSlotsPerLine) : 0;
     const uint32_t line1 = need1 ? ext_line(e) : 0u;
     const uint32_t par1 = (uint32_t)lane | ((uint32_t)n_e << 8) | ((uint32_t)f << 16) | (1u << 24);
@@ -529,7 +528,7 @@ __global__ void __launch_bounds__(256, 5) tns_sample_prefix_kernel(const SampleA
     }
     // Fan-outs up to ten: everything goes through the rows (walked queries: rotation 0 after walked_gather).
     // Larger fan-outs: every query walked, the rows hold positions, the output stage gathers from memory.
-    const bool row_path = f <= kMaxFastFanout;
+    const bool row_path = POLICY == 0 && f <= kMaxFastFanout;
     const int32_t info = k | ((walked ? 0 : rot) << 8);
     const int32_t pstride = (int32_t)(rs * 4 / (int)sizeof(pos_t));     // row stride in positions
     const pos_t* __restrict__ w_pos = reinterpret_cast<const pos_t*>(rows);
@@ -541,13 +540,12 @@ __global__ void __launch_bounds__(256, 5) tns_sample_prefix_kernel(const SampleA
         ScanWorkspace* ws = static_cast<ScanWorkspace*>(p.scan_ws);
         const int32_t inc = wave_inclusive_scan(k, lane);
         auto publish_total = [&](int32_t wg_total) {
+            // the tile total is published at once, so that later tiles can look past this one
             if (lane == 0 && tile > 0)
                 __hip_atomic_store(&ws->status[tile], kStTotal | (uint64_t)wg_total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         };
-        auto chain = [&](int32_t wg_total) {
-            int64_t excl = 0;
-            if (p.exp & 16) excl = p.rowptr[min(tile * (int64_t)waves_per_wg * kWave, Q - 1)];      // experiment: offsets of an earlier identical run
-            else if (tile > 0 && !(p.exp & 1)) excl = lookback_exclusive(ws, p.err_flag, tile, lane);
+        auto chain = [&](int32_t wg_total) {      // one wave: look back for the tile's offset, publish the prefix
+            const int64_t excl = tile > 0 ? lookback_exclusive(ws, p.err_flag, tile, lane) : 0;
             if (lane == 0) {
                 __hip_atomic_store(&ws->status[tile], kStPrefix | (uint64_t)(excl + wg_total), __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
@@ -589,15 +587,17 @@ __global__ void __launch_bounds__(256, 5) tns_sample_prefix_kernel(const SampleA
                 publish_total(wg_total);
             }
             if (row_path) rows_load(g, p, f_magic, rows, rs, lane, info);
-            else gather_load(g, p, f_magic, pstride, w_pos, lane, 0, k);
-            // The look-back reads come before this wave's stores: a load result can only be waited for
-            // together with every store issued before it, and a store takes microseconds to be taken.
-            if (is_last) chain(wg_total);
-            if (!(p.exp & 4)) store_padded(g, p, f_magic, lane, 0, q0, Q);
+            else gather_load<pos_t, POLICY == 1>(g, p, f_magic, pstride, w_pos, lane, 0, k);
+            // Recent policy: the look-back reads come before this wave's stores (a load result can only be
+            // waited for together with every store issued before it, and a store takes microseconds to be
+            // taken).  Uniform policy: the other order measured faster, as in the other kernel.
+            if (is_last && POLICY == 0) chain(wg_total);
+            store_padded(g, p, f_magic, lane, 0, q0, Q);
+            if (is_last && POLICY != 0) chain(wg_total);
             lds_barrier();
             const int64_t row = s_tile_base + offset_of_wave() + (inc - k);
             write_rowptr(row);
-            if (!(p.exp & 2)) store_dense(g, p, f_magic, lane, 0, row);
+            store_dense(g, p, f_magic, lane, 0, row);
         } else {
             if (lane == kWave - 1) s_wave_sum[wave] = inc;
             __syncthreads();
@@ -611,7 +611,7 @@ __global__ void __launch_bounds__(256, 5) tns_sample_prefix_kernel(const SampleA
             const int64_t row = s_tile_base + offset_of_wave() + (inc - k);
             write_rowptr(row);
             for (int32_t it0 = 0; it0 < f; it0 += kGatherChunk) {      // larger fan-outs: positions in the rows
-                gather_load(g, p, f_magic, pstride, w_pos, lane, it0, k);
+                gather_load<pos_t, POLICY == 1>(g, p, f_magic, pstride, w_pos, lane, it0, k);
                 store_padded(g, p, f_magic, lane, it0, q0, Q);
                 store_dense(g, p, f_magic, lane, it0, row);
             }
@@ -620,10 +620,10 @@ __global__ void __launch_bounds__(256, 5) tns_sample_prefix_kernel(const SampleA
         GatherRegs g;
         if (row_path) {
             rows_load(g, p, f_magic, rows, rs, lane, info);
-            if (!(p.exp & 4)) store_padded(g, p, f_magic, lane, 0, q0, Q);
+            store_padded(g, p, f_magic, lane, 0, q0, Q);
         } else {
             for (int32_t it0 = 0; it0 < f; it0 += kGatherChunk) {
-                gather_load(g, p, f_magic, pstride, w_pos, lane, it0, k);
+                gather_load<pos_t, POLICY == 1>(g, p, f_magic, pstride, w_pos, lane, it0, k);
                 store_padded(g, p, f_magic, lane, it0, q0, Q);
             }
         }
@@ -636,7 +636,7 @@ inline uint32_t magic_of(int32_t f) { return f <= 1 ? 0u : (uint32_t)(((uint64_t
 template <int POLICY, bool INCL, typename pos_t, bool COUNT, bool FUSED>
 hipError_t launch_prefix_t(const SampleArgs& a, hipStream_t stream) {
     const int32_t f = a.fanout;
-    const bool fast_rows = f <= kMaxFastFanout;                      // rows hold edges (3 words per slot)
+    const bool fast_rows = POLICY == 0 && f <= kMaxFastFanout;       // rows hold edges (3 words per slot)
     // row stride in 4-byte words: odd (conflict-free per-lane rows) for 32-bit contents, even when the row
     // holds 64-bit positions
     int32_t rs;
@@ -646,12 +646,16 @@ hipError_t launch_prefix_t(const SampleArgs& a, hipStream_t stream) {
     const int32_t gshift = (POLICY == 0 && f <= kCoopGroup) ? 4 : -1;
     // per wave: result rows, then 256 bytes for the line requests' owners and counts (the counts of the walking
     // lanes' cooperative searches); at least the 4 KiB in which the node lines are staged first, 32 at a time
-    static const size_t pad = [] { const char* v = std::getenv("TNS_PREFIX_PAD"); return v ? (size_t)std::atoi(v) : (size_t)0; }();
-    const size_t chunk = std::max<size_t>(rows_bytes + kExtraLds, 4096) + pad;
-    // the kernel is compiled for workgroups of up to four waves; the chained scan wants them large, without it
-    // smaller workgroups come and go more evenly (C5 at 2^26 queries: 4.33 / 4.43 / 4.87 ms with 1 / 2 / 4 waves)
-    int waves = a.prefix_waves > 0 ? std::min(a.prefix_waves, 4) : (FUSED ? 4 : 2);
-    while (waves > 1 && (size_t)waves * chunk > (size_t)(64u << 10)) --waves;      // dynamic LDS of a workgroup: 64 KiB at most
+    const size_t chunk = std::max<size_t>(rows_bytes + kExtraLds, 4096);
+    // Workgroup size.  With the padding removal fused in, a workgroup is a tile of the chained scan: tiles
+    // finish out of order (a tile of four waves is on average several hundred tiles ahead of the oldest
+    // unfinished one when it has its total, and waits about as long as it sampled), so large tiles win
+    // although a compute unit then holds a single workgroup (C5 at 2^26 queries, recent: 7.98 / 7.56 / 6.79 ms
+    // with 4 / 8 / 16 waves; uniform: 7.10 / 6.91 / 7.83).  Without the scan small workgroups come and go more
+    // evenly (4.33 / 4.43 / 4.87 / 6.17 ms with 1 / 2 / 4 / 16 waves).
+    int waves = FUSED ? (POLICY == 0 ? 16 : 8) : 2;
+    while (waves > 1 && (size_t)waves * chunk > (size_t)(159u << 10)) --waves;      // LDS of a workgroup: 160 KiB
+    // small batches: smaller workgroups, so that the queries spread over the compute units
     while (waves > 1 && (a.Q + (int64_t)waves * kWave - 1) / ((int64_t)waves * kWave) < 512) waves >>= 1;
     const int64_t per_wg = (int64_t)waves * kWave;
     const int64_t grid = (a.Q + per_wg - 1) / per_wg;

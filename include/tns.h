@@ -4,12 +4,12 @@
  *
  * The operations follow GNNFlow (arXiv 2311.17410):
  *   - the store is the node table + per-node chronological list of edge blocks of
- *     section 4.1, with the block size rule b_v = min(deg(v), tau) ("Adaptive block sizing
- *     with threshold");
+ *     section 4.1, with the block size rule b_v = min(deg(v), tau) (the paragraph on adaptive
+ *     block sizing);
  *   - tns_run executes Algorithm 1 (section 4.2) for a batch of queries, with the recent
  *     and uniform selection policies of section 2.1, writes the padded per-target result the
- *     way section 4.2 "Kernel optimizations" asks for (consecutive slots per target) and
- *     optionally removes the padding (section 5, "GPU-based sampling").
+ *     way the kernel-optimization paragraph of section 4.2 asks for (consecutive slots per
+ *     target) and optionally removes the padding (section 5, the paragraph on GPU sampling).
  *
  * Conventions
  *   - Plain C ABI.  Every pointer argument is marked HOST or DEVICE.  DEVICE pointers are
@@ -62,11 +62,11 @@ enum {
     TNS_FLAG_NO_NODE_SLAB = 2, /* do not reserve one 128-byte edge line per non-empty node for its first
                                   blocks: less memory for graphs of mostly degree-1 nodes, more lines
                                   read per query                                                        */
-    /* Placement (section 4.1, "hybrid GPU-CPU graph data placement").  Default: node table, block
+    /* Placement (section 4.1, the paragraph on placing graph data across GPU and CPU memory).  Default: node table, block
        records and edge data all in device memory.  EDGES_ON_HOST is the paper's hybrid placement:
        the metadata (node table, block records) in device memory, the edge data in page-locked host
        memory that the kernels read across the host link.  ALL_ON_HOST puts the metadata there too
-       (the paper's "UVA-only" comparison point).  Results are identical under all three. */
+       (the all-in-host-memory comparison point of the paper's sampling ablation).  Results are identical under all three. */
     TNS_FLAG_EDGES_ON_HOST = 4,
     TNS_FLAG_ALL_ON_HOST = 8,
     /* The store is built on the device: batches come from device memory through

@@ -70,6 +70,8 @@ def lib():
         L.bs_sample.argtypes = [C.c_void_p, C.c_int64, i32p, f32p, f32p, i64p, C.c_int32, C.c_int32,
                                 C.c_int32, C.c_uint64, i32p, i32p, f32p, i32p]
         L.bs_sample.restype = C.c_int
+        L.bs_walk_counts.argtypes = [C.c_void_p, C.c_int64, i32p, f32p, f32p, C.c_int32, C.c_int32, C.c_int32, i64p]
+        L.bs_walk_counts.restype = C.c_int
         L.bs_stats.argtypes = [C.c_void_p, C.POINTER(C.c_double), i64p, i64p, i64p, i64p, i64p]
         L.bs_stats.restype = C.c_int
         L.bs_export_blocks.argtypes = [C.c_void_p, i32p, i64p, i64p, f32p, f32p]
@@ -209,6 +211,17 @@ class BlockStore:
         if rc:
             raise OracleError(rc, "bs_sample")
         return out
+
+    def walk_counts(self, targets, t_start, t_end, fanout, policy=0, inclusive_end=0) -> dict:
+        """What Algorithm 1's walk touches over a batch: node entries, block metadata records, timestamps compared
+        by the bound searches, edges selected (the per-query quantities of a byte model, summed)."""
+        targets, t_start, t_end = _arr(targets, np.int32), _arr(t_start, np.float32), _arr(t_end, np.float32)
+        tot = np.zeros(4, np.int64)
+        rc = lib().bs_walk_counts(self._h, targets.shape[0], _p(targets, C.c_int32), _p(t_start, C.c_float),
+                                  _p(t_end, C.c_float), fanout, policy, inclusive_end, _p(tot, C.c_int64))
+        if rc:
+            raise OracleError(rc, "bs_walk_counts")
+        return dict(nodes=int(tot[0]), blocks=int(tot[1]), probes=int(tot[2]), edges=int(tot[3]))
 
     def stats(self) -> dict:
         avg = C.c_double()

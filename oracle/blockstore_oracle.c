@@ -15,10 +15,10 @@
  * batch brings node v more edges than its tail block can take, the tail is filled and ONE
  * new block is allocated for the remaining m' edges, with capacity
  *      adaptive :  max(m', min(deg_at_allocation, tau))
- *      strawman :  m'                      (section 6.2: "number of new edges to add")
+ *      strawman :  m'                      (section 6.2: exactly as many slots as the batch brings)
  *      fixed    :  ceil(m'/tau) blocks of capacity tau  (section 6.2, PlatoGL style)
  * where deg_at_allocation counts the edges already stored including those that just
- * filled the tail.  Table "Linked list length and memory usage" supports the one-block-
+ * filled the tail.  The table of list lengths and memory usage in section 6.2 supports the one-block-
  * per-batch reading (adaptive max list length 1896 ~ number of 100k batches in GDELT).
  *
  * Parity pins: tests/test_blockstore_oracle.py (sizing closed forms, structural
@@ -189,13 +189,17 @@ int bs_delete_edge(bs_store *s, int32_t node, int32_t eid)
     return hit;
 }
 
-static int64_t lower_pos(const float *ts, int64_t n, float x, int strict)
+/* searches counted for bs_walk_counts: one per timestamp a bound search compares */
+static int64_t g_unused_probe_sink;
+
+static int64_t lower_pos(const float *ts, int64_t n, float x, int strict, int64_t *probes)
 {
     /* first i with ts[i] >= x (strict=0) or ts[i] > x (strict=1) */
     int64_t lo = 0, hi = n;
     while (lo < hi) {
         int64_t mid = lo + (hi - lo) / 2;
         int ge = strict ? (ts[mid] > x) : (ts[mid] >= x);
+        ++*probes;
         if (ge) hi = mid; else lo = mid + 1;
     }
     return lo;
@@ -210,13 +214,65 @@ static uint64_t bs_pick(uint64_t seed, int64_t q, int32_t f, int32_t j, uint64_t
     return ((z >> 32) * c) >> 32;
 }
 
-typedef struct { const bs_block *b; int64_t i; } cand;
+typedef struct { const bs_block *b; int64_t lo, hi; } span;   /* candidates [lo, hi) of one block */
 
 /*
- * Algorithm 1 for a batch of queries: start at the node's newest block, step to prev
- * while the block lies after the window, stop when it lies before it, otherwise search
- * the window inside the block and collect the candidates; finally select f of them.
- * Deleted edges are dropped from the candidates before selection.
+ * Phase 1 of Algorithm 1 for one query: the block list of node v is followed from the newest
+ * block towards older ones, using only each block's (t_min, t_max).  A block that starts after
+ * the window contributes nothing and is passed over; the first block that ends before the
+ * window ends the walk, since every older block ends earlier still.  What remains are the blocks
+ * overlapping [tb, te], newest first.  `examined` receives the number of blocks whose metadata
+ * was looked at.  Returns the number of overlapping blocks, or -1 when out of memory.
+ */
+static int64_t overlapping(const bs_node *nd, float tb, float te, span **sp, int64_t *cap, int64_t *examined)
+{
+    int64_t n = 0;
+    for (const bs_block *b = nd->tail; b; b = b->prev) {
+        ++*examined;
+        if (b->t_max < tb) break;
+        if (b->t_min > te) continue;
+        if (n == *cap) {
+            span *n2 = (span *)realloc(*sp, (size_t)(*cap * 2) * sizeof(span));
+            if (!n2) return -1;
+            *sp = n2; *cap *= 2;
+        }
+        (*sp)[n].b = b; (*sp)[n].lo = 0; (*sp)[n].hi = 0; n++;
+    }
+    return n;
+}
+
+/* Phase 2: both window bounds are located in a block's sorted timestamps (section 4.1: the
+ * sorted order is what allows a logarithmic search). */
+static void search_span(span *s, float tb, float te, int inclusive_end, int64_t *probes)
+{
+    s->lo = lower_pos(s->b->ts, s->b->size, tb, 0, probes);
+    s->hi = lower_pos(s->b->ts, s->b->size, te, inclusive_end, probes);
+    if (s->hi < s->lo) s->hi = s->lo;
+}
+
+static int64_t live_in(const span *s)
+{
+    int64_t c = 0;
+    for (int64_t i = s->lo; i < s->hi; ++i) c += s->b->present[i] ? 1 : 0;
+    return c;
+}
+
+/* the r-th newest live candidate over the spans (r = 0: the newest) */
+static void nth_newest(const span *sp, int64_t n, int64_t r, const bs_block **b, int64_t *i)
+{
+    for (int64_t t = 0; t < n; ++t)
+        for (int64_t x = sp[t].hi - 1; x >= sp[t].lo; --x) {
+            if (!sp[t].b->present[x]) continue;
+            if (r-- == 0) { *b = sp[t].b; *i = x; return; }
+        }
+    *b = NULL; *i = -1;
+}
+
+/*
+ * Algorithm 1 for a batch of queries, in its three phases: the overlapping blocks of the target
+ * (walk over block metadata), the candidate range inside each of them (binary searches), the
+ * selection of at most f candidates (section 2.1: the newest ones, or uniform picks among all).
+ * Deleted edges are not candidates.
  */
 int bs_sample(const bs_store *s, int64_t Q, const int32_t *targets, const float *t_start,
               const float *t_end, const int64_t *q_ids, int32_t f, int32_t policy,
@@ -224,48 +280,69 @@ int bs_sample(const bs_store *s, int64_t Q, const int32_t *targets, const float 
               float *out_ts, int32_t *out_count)
 {
     if (!s || Q < 0 || f <= 0) return BS_EINVAL;
-    int64_t capc = 1024;
-    cand *cs = (cand *)malloc((size_t)capc * sizeof(cand));
-    if (!cs) return BS_ENOMEM;
+    int64_t cap = 64;
+    span *sp = (span *)malloc((size_t)cap * sizeof(span));
+    if (!sp) return BS_ENOMEM;
     for (int64_t q = 0; q < Q; ++q) {
-        int64_t c = 0;                      /* candidates, collected newest block first,      */
-        int64_t v = targets[q];             /* inside a block newest edge first               */
+        int64_t v = targets[q], n = 0, c = 0, unused = 0;
         float te = t_end[q], tb = t_start ? t_start[q] : -INFINITY;
         if (v >= 0 && v < s->num_nodes && s->nodes[v].valid && !isnan(te) && !isnan(tb)) {
-            const bs_block *b = s->nodes[v].tail;
-            while (b) {
-                if (te < b->t_min) { b = b->prev; continue; }
-                if (tb > b->t_max) break;
-                int64_t lo = lower_pos(b->ts, b->size, tb, 0);
-                int64_t hi = lower_pos(b->ts, b->size, te, inclusive_end);
-                for (int64_t i = hi - 1; i >= lo; --i) {
-                    if (!b->present[i]) continue;
-                    if (c == capc) {
-                        capc *= 2;
-                        cand *n2 = (cand *)realloc(cs, (size_t)capc * sizeof(cand));
-                        if (!n2) { free(cs); return BS_ENOMEM; }
-                        cs = n2;
-                    }
-                    cs[c].b = b; cs[c].i = i; c++;
-                }
-                b = b->prev;
+            n = overlapping(&s->nodes[v], tb, te, &sp, &cap, &unused);
+            if (n < 0) { free(sp); return BS_ENOMEM; }
+            for (int64_t t = 0; t < n; ++t) {
+                search_span(&sp[t], tb, te, inclusive_end, &g_unused_probe_sink);
+                c += live_in(&sp[t]);
             }
         }
-        /* cs[0] is the newest candidate, cs[c-1] the oldest */
         int64_t k = c < f ? c : f;
         int64_t qid = q_ids ? q_ids[q] : q;
         for (int64_t j = 0; j < f; ++j) {
             int32_t *on = out_nbr + q * f + j, *oe = out_eid + q * f + j;
             float *ot = out_ts + q * f + j;
             if (j >= k) { *on = -1; *oe = -1; *ot = 0.0f; continue; }
-            int64_t r;                                       /* index into cs */
-            if (policy == 0 || c <= f) r = j;
-            else r = c - 1 - (int64_t)bs_pick(seed, qid, f, (int32_t)j, (uint64_t)c);  /* rank counted from the oldest */
-            *on = cs[r].b->nbr[cs[r].i]; *oe = cs[r].b->eid[cs[r].i]; *ot = cs[r].b->ts[cs[r].i];
+            int64_t r = j;                                   /* distance from the newest candidate */
+            if (policy != 0 && c > f)                        /* the pick is a rank counted from the oldest */
+                r = c - 1 - (int64_t)bs_pick(seed, qid, f, (int32_t)j, (uint64_t)c);
+            const bs_block *b; int64_t i;
+            nth_newest(sp, n, r, &b, &i);
+            *on = b->nbr[i]; *oe = b->eid[i]; *ot = b->ts[i];
         }
         out_count[q] = (int32_t)k;
     }
-    free(cs);
+    free(sp);
+    return BS_OK;
+}
+
+/*
+ * What the walk of Algorithm 1 touches, summed over a batch of queries (the quantities of a
+ * bytes-per-query model): totals[0] = node entries looked up (queries with a valid target),
+ * totals[1] = blocks whose metadata is examined, totals[2] = timestamps compared by the bound
+ * searches (both bounds in every overlapping block that is searched), totals[3] = edges selected.
+ * Under the recent policy the walk ends as soon as f live candidates are known, since older blocks
+ * cannot displace them; under the uniform policy every overlapping block is searched.
+ */
+int bs_walk_counts(const bs_store *s, int64_t Q, const int32_t *targets, const float *t_start,
+                   const float *t_end, int32_t f, int32_t policy, int32_t inclusive_end, int64_t *totals)
+{
+    if (!s || Q < 0 || f <= 0 || !totals) return BS_EINVAL;
+    totals[0] = totals[1] = totals[2] = totals[3] = 0;
+    for (int64_t q = 0; q < Q; ++q) {
+        int64_t v = targets[q];
+        float te = t_end[q], tb = t_start ? t_start[q] : -INFINITY;
+        if (!(v >= 0 && v < s->num_nodes && s->nodes[v].valid) || isnan(te) || isnan(tb)) continue;
+        totals[0]++;
+        int64_t c = 0;
+        for (const bs_block *b = s->nodes[v].tail; b; b = b->prev) {
+            totals[1]++;
+            if (b->t_max < tb) break;
+            if (b->t_min > te) continue;
+            span one = { b, 0, 0 };
+            search_span(&one, tb, te, inclusive_end, &totals[2]);
+            c += live_in(&one);
+            if (policy == 0 && c >= f) break;
+        }
+        totals[3] += c < f ? c : f;
+    }
     return BS_OK;
 }
 

@@ -10,21 +10,22 @@
  * edge sits), so this file uses no blocks at all.  It writes the result out from its
  * definition:
  *
- *   O1  per-node chronological edge lists        section 4.1, "graph edge data ...
- *                                                organized in increasing order of edge
- *                                                timestamps"; directed edges are stored
- *                                                with their source node (footnote there)
- *   O2  candidate window [t_s, t_e)              Algorithm 1, the "find neighbors within
- *                                                time window" step; closed upper bound
- *                                                [t - delta, t] of section 2.1 as option
- *   O3  selection: recent / uniform              section 2.1 ("recent sampling ... closest
- *                                                to the given timestamp", "uniform
- *                                                sampling ... randomly selects a subset")
- *   O4  padded result, f slots per target        section 4.2 "kernel optimizations"
- *                                                (consecutive results per target)
- *   O5  removal of the padding                   section 5, "GPU-based sampling"
+ *   O1  per-node chronological edge lists        section 4.1: a node's edge data is kept
+ *                                                in increasing timestamp order; a directed
+ *                                                edge is stored with its source node
+ *                                                (footnote there)
+ *   O2  candidate window [t_s, t_e)              Algorithm 1, the step that finds the
+ *                                                neighbours inside the time window; the
+ *                                                closed upper bound [t - delta, t] of
+ *                                                section 2.1 as an option
+ *   O3  selection: recent / uniform              section 2.1: recent keeps the neighbours
+ *                                                nearest in time to the query timestamp,
+ *                                                uniform draws a random subset of all
+ *   O4  padded result, f slots per target        section 4.2, kernel optimizations
+ *                                                (a target's results lie side by side)
+ *   O5  removal of the padding                   section 5, the paragraph on GPU sampling
  *
- * Tie rule (the paper only says "increasing order"): order is (timestamp, arrival);
+ * Tie rule (the paper fixes the order by timestamp only): order is (timestamp, arrival);
  * among equal timestamps the later arrival is the more recent one.
  * Uniform sampling draws with replacement from a counter-based generator keyed by
  * (seed, query id, slot); the paper fixes neither, see oracle_pick().
@@ -62,8 +63,8 @@ void oracle_adj_free(ora_adj *a)
  *
  *   eid          NULL: edge i has id i
  *   present      NULL: every edge exists; else present[i]==0 marks a deleted edge, which is
- *                treated as absent (section 4.1: "Invalid nodes/edges are ignored during
- *                sampling")
+ *                treated as absent (section 4.1: entries marked invalid take no part in
+ *                sampling)
  *   batch_rowptr NULL: the whole stream is one ingestion batch; else [num_batches+1]
  *                offsets.  Edges of one node inside one batch are put in timestamp order
  *                (stable: equal times keep arrival order); a batch that brings a node an

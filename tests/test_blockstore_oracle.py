@@ -182,3 +182,25 @@ def test_deletion_filters_before_selection(oracle_lib):
         a = adj.sample(targets, t_start, t_end, fanout=5, policy=pol, seed=2)
         b = bs.sample(targets, t_start, t_end, fanout=5, policy=pol, seed=2)
         assert np.array_equal(a.eid, b.eid) and np.array_equal(a.count, b.count)
+
+
+def test_walk_counts_closed_form(oracle_lib):
+    """One edge per block (fixed sizing, tau = 1), node 0 gets n edges at times 1..n.  A query after all of them
+    with fan-out f: the recent walk examines f blocks (one candidate each), the exhaustive walk all n; every
+    searched one-edge block costs one comparison per bound.  A query at time j + 0.5 first steps over the
+    n - j newer blocks."""
+    n, f = 12, 3
+    bs = oracle_lib.BlockStore(4, 1, oracle_lib.BlockStore.FIXED)
+    for i in range(n):
+        bs.add_batch([0], [1], [float(i + 1)])
+    assert bs.stats()["num_blocks"] == n
+    q = lambda t, pol, tb=None: bs.walk_counts([0], tb, [t], f, policy=pol)
+    assert q(100.0, 0) == dict(nodes=1, blocks=f, probes=2 * f, edges=f)
+    assert q(100.0, 1) == dict(nodes=1, blocks=n, probes=2 * n, edges=f)
+    j = 5
+    assert q(j + 0.5, 0) == dict(nodes=1, blocks=(n - j) + f, probes=2 * f, edges=f)
+    # window [j - 0.5, j + 0.5]: one candidate, and the walk ends at the first block before the window
+    assert q(j + 0.5, 0, [j - 0.5]) == dict(nodes=1, blocks=(n - j) + 2, probes=2, edges=1)
+    # unknown or empty targets look nothing up / find nothing
+    assert bs.walk_counts([9, 2], None, [1.0, 1.0], f) == dict(nodes=0 + 1, blocks=0, probes=0, edges=0)
+    bs.close()

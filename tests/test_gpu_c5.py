@@ -1,8 +1,8 @@
 """C5 at full size (n = 2^28 events = queries, |V| = 2^24), in the launch configuration
-bench.py times: one tns_run with the dense outputs over the whole batch.  The recent policy is
-compared with the oracle on EVERY query (in chunks of 2^24, so the host never holds the 32 GB
-padded result); the uniform policy and the windowed variant on sampled chunks; plus the
-size-independent invariants."""
+bench.py times: one tns_run with the dense outputs over the whole batch.  Every variant (recent,
+uniform, windowed, the device-built store, and both policies on the prefix layout) is compared
+with the oracle on EVERY query, in chunks of 2^24 so the host never holds the 32 GB padded
+result; plus the size-independent invariants on two chunks."""
 import numpy as np
 import pytest
 
@@ -100,31 +100,36 @@ def check_invariants_chunk(st, lo, hi, ref, f):
     assert np.all(ref.eid[~filled] == -1) and np.all(ref.nbr[~filled] == -1) and np.all(ref.ts[~filled] == 0)
 
 
-def test_c5_uniform_sampled_chunks(c5):
+def _compare_all(c5, label, policy, t_start_np, seed):
+    st = c5["st"]
+    row = 0
+    for c in range((st.n + CHUNK - 1) // CHUNK):
+        row, _ = _compare_chunk(c5, c, policy, t_start_np, seed, row)
+        progress(f"{label}: chunk {c} matches")
+    assert int(c5["out"]["rowptr"][st.n].item()) == row
+
+
+def test_c5_uniform_every_query(c5):
     B = c5["B"]
     c5["plan"].set_sampler(c5["wl"].fanout, B.TNS_POLICY_UNIFORM, 0, 4)
     progress("C5 uniform: GPU run over 2^28 queries")
     _run(c5)
-    for c in (0, 7, 15):
-        _compare_chunk(c5, c, 1, None, 4, None)
-        progress(f"C5 uniform: chunk {c} matches")
+    _compare_all(c5, "C5 uniform", 1, None, 4)
 
 
-def test_c5_windowed_sampled_chunks(c5):
+def test_c5_windowed_every_query(c5):
     B, st, torch = c5["B"], c5["st"], c5["torch"]
     c5["plan"].set_sampler(c5["wl"].fanout, B.TNS_POLICY_RECENT, 0, 0)
     t_start = (st.ts - np.float32(0.25) * np.float32(st.ts[-1] - st.ts[0])).astype(np.float32)
     d_tb = torch.from_numpy(t_start).to(c5["d"]["t_end"].device)
     progress("C5 windowed: GPU run over 2^28 queries")
     _run(c5, d_tb)
-    for c in (3, 12):
-        _compare_chunk(c5, c, 0, t_start, 0, None)
-        progress(f"C5 windowed: chunk {c} matches")
+    _compare_all(c5, "C5 windowed", 0, t_start, 0)
 
 
 def test_c5_store_built_on_the_device(c5):
     """The same stream ingested on the GPU (tns_add_edges_device, 2^17-edge batches): same block
-    statistics as the host builder, and the full-size run matches the oracle on sampled chunks."""
+    statistics as the host builder, and the full-size run matches the oracle on every query."""
     B, st, torch, wl = c5["B"], c5["st"], c5["torch"], c5["wl"]
     dplan = B.Plan(st.num_nodes, wl.fanout, block_threshold=wl.tau, flags=B.TNS_FLAG_DEVICE_INGEST)
     d_dst = torch.from_numpy(st.dst).to(c5["d"]["t_end"].device)
@@ -140,8 +145,30 @@ def test_c5_store_built_on_the_device(c5):
     progress("C5 device-built: GPU run over 2^28 queries")
     dplan.run(c5["d"]["targets"], None, c5["d"]["t_end"], out=c5["out"])
     torch.cuda.synchronize()
-    assert not c5["plan"].status(c5["out"]["workspace"])
-    for c in (2, 14):
-        _compare_chunk(c5, c, 0, None, 0, None)
-        progress(f"C5 device-built: chunk {c} matches")
+    assert not dplan.status(c5["out"]["workspace"])
+    _compare_all(c5, "C5 device-built", 0, None, 0)
     dplan.close()
+
+
+def test_c5_prefix_layout_every_query(c5):
+    """The same stream in the prefix layout (TNS_FLAG_PREFIX_LAYOUT): same block statistics as the default layout,
+    and both policies match the oracle on every query of the full-size run."""
+    B, st, torch, wl = c5["B"], c5["st"], c5["torch"], c5["wl"]
+    pplan = B.Plan(st.num_nodes, wl.fanout, block_threshold=wl.tau, flags=B.TNS_FLAG_PREFIX_LAYOUT)
+    progress("C5 prefix layout: ingesting 2^28 edges")
+    for i, (lo, hi) in enumerate(st.batches()):
+        B.tns_add_edges(pplan.handle, 0, st.src[lo:hi], st.dst[lo:hi], st.ts[lo:hi], None)
+        if i % 512 == 511:
+            progress(f"C5 prefix layout: {hi} edges ingested")
+    pplan.commit()
+    hs, ps = c5["plan"].stats(), pplan.stats()
+    for k in ("num_blocks", "num_edges", "wasted_slots", "max_list_len"):
+        assert hs[k] == ps[k], k
+    for label, policy, seed in (("C5 prefix recent", B.TNS_POLICY_RECENT, 0), ("C5 prefix uniform", B.TNS_POLICY_UNIFORM, 4)):
+        pplan.set_sampler(wl.fanout, policy, 0, seed)
+        progress(f"{label}: GPU run over 2^28 queries")
+        pplan.run(c5["d"]["targets"], None, c5["d"]["t_end"], out=c5["out"])
+        torch.cuda.synchronize()
+        assert not pplan.status(c5["out"]["workspace"])
+        _compare_all(c5, label, 1 if policy == B.TNS_POLICY_UNIFORM else 0, None, seed)
+    pplan.close()

@@ -155,7 +155,10 @@ TNS_API int tns_add_edges_device(tns_plan *plan, int32_t instance, const int32_t
  * stored edges matched.  Edge ids must therefore be non-negative (tns_add_edges rejects negative
  * ids): the store marks a deleted edge by complementing its id.  Cost: a scan of the node's
  * edges per pair on the host; on the device, a query that meets a block holding deleted edges
- * checks that block's candidates one by one.  For a store built on the device
+ * checks that block's candidates one by one, and once a plan has deleted an edge tns_run removes
+ * the padding in a step of its own (sampling kernel, then the kernels of tns_compact) instead of in
+ * the sampling kernel: a slow query then delays nothing but itself.  tns_run_khop keeps the one-pass
+ * form and reports a time-out through tns_run_status.  For a store built on the device
  * (TNS_FLAG_DEVICE_INGEST) both calls copy the requests over, apply them with a kernel on the
  * default stream and wait for it: they take effect at once, without tns_commit.
  *

@@ -2,8 +2,8 @@
  * TEST INFRASTRUCTURE -- not part of the product path.
  *
  * Second, structural oracle: the paper's time-indexed block store (section 4.1) built
- * with real heap blocks and pointers, and Algorithm 1 walked over it step by step
- * (section 4.2).  It exists to check (a) that sampling results do not depend on the
+ * with real heap blocks and pointers, and Algorithm 1 over it in three phases (overlapping blocks, bound searches, selection;
+ * section 4.2).  It exists to check (a) that sampling results do not depend on the
  * block layout, by agreeing with the layout-free definition in tns_oracle.c, and (b) the
  * layout facts themselves (block sizes, list lengths, wasted slots).  It shares no code
  * with tns_oracle.c or with the HIP library.

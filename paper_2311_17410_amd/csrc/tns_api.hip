@@ -66,6 +66,7 @@ struct DeviceStore {
     DeviceArray<tns::NodeAux> aux;
     DeviceArray<unsigned char> ws;              // scratch of the ingestion kernels, grown on demand
     tns::IngestStatus* d_status = nullptr;
+    tns::IngestStatus* h_status = nullptr;      // page-locked landing place of the status read-backs
     std::vector<tns::InstanceTotals> totals;   // per instance: edges, blocks, slots, running edge id, deleted
 };
 
@@ -82,6 +83,7 @@ struct tns_plan {
     DeviceArray<uint32_t> d_dir_cum;            // per directory record: the node's edges in older blocks
     DeviceArray<tns::EdgeLine> d_edges;
     bool committed = false;
+    bool deleted_edges = false;                 // some edge has been deleted: blocks with deleted edges are scanned candidate by candidate
 };
 
 namespace {
@@ -164,6 +166,9 @@ int ensure_device_store(tns_plan* plan, hipStream_t stream) {
     if (e == hipSuccess) e = hipMemsetAsync(ds.aux.ptr, 0, (size_t)total_nodes * sizeof(tns::NodeAux), stream);
     tns::IngestStatus* st = nullptr;
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&st), sizeof(tns::IngestStatus));
+    if (e == hipSuccess && !ds.h_status) e = hipHostMalloc(reinterpret_cast<void**>(&ds.h_status), sizeof(tns::IngestStatus), hipHostMallocDefault);
+    if (e == hipSuccess) e = hipMemsetAsync(st, 0, sizeof(tns::IngestStatus), stream);
+    if (e == hipSuccess) e = tns::ingest_status_reset(st, stream);
     if (e == hipSuccess) e = hipStreamSynchronize(stream);
     if (e != hipSuccess) {
         if (st) (void)hipFree(st);
@@ -176,10 +181,24 @@ int ensure_device_store(tns_plan* plan, hipStream_t stream) {
     return TNS_OK;
 }
 
+// Waits for the stream and returns the builder's status record.  A set `internal` word (a pool found too small by
+// an apply kernel, or a chained scan whose bounded wait ran out) is an error of the library, reported here by
+// whichever call reads the record next; the record is then made clean again.
 int read_status(tns_plan* plan, hipStream_t stream, tns::IngestStatus& out, const char* what) {
-    hipError_t e = hipMemcpyAsync(&out, plan->dev->d_status, sizeof(out), hipMemcpyDeviceToHost, stream);
+    DeviceStore& ds = *plan->dev;
+    hipError_t e = hipMemcpyAsync(ds.h_status, ds.d_status, sizeof(out), hipMemcpyDeviceToHost, stream);
     if (e == hipSuccess) e = hipStreamSynchronize(stream);
     if (e != hipSuccess) return fail_hip(e, what);
+    out = *ds.h_status;
+    if (out.internal) {
+        const uint32_t bits = out.internal;
+        e = hipMemsetAsync(ds.d_status, 0, sizeof(out), stream);
+        if (e == hipSuccess) e = tns::ingest_status_reset(ds.d_status, stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(stream);
+        if (e != hipSuccess) return fail_hip(e, what);
+        return fail(TNS_EHIP, bits & 8u ? "a chained scan of the ingestion kernels timed out (internal error); the batch was not applied"
+                                        : "ingestion kernels of an earlier batch ran out of pool space (internal error)");
+    }
     return TNS_OK;
 }
 
@@ -349,10 +368,22 @@ int tns_add_edges_device(tns_plan* plan, int32_t instance, const int32_t* d_src,
     a.workspace = ds.ws.ptr;
     a.status = ds.d_status;
 
-    hipError_t e = tns::ingest_plan(a, stream);
+    // Batches of stream size take the short planning pipeline, which assumes time order; if the status says the
+    // batch was not in time order (nothing has been changed yet) the general pipeline plans it again.
+    bool fast = tns::ingest_fast_ok(m, plan->cfg.num_nodes);
+    hipError_t e = fast ? tns::ingest_plan_fast(a, stream) : tns::ingest_plan(a, stream);
     if (e != hipSuccess) return fail_hip(e, "launching the ingestion planning kernels");
     tns::IngestStatus st;
     if ((rc = read_status(plan, stream, st, "waiting for the ingestion plan"))) return rc;
+    if (fast && st.unsorted && st.err_word == ~0ull) {
+        fast = false;
+        if ((e = tns::ingest_plan(a, stream)) != hipSuccess) return fail_hip(e, "launching the ingestion planning kernels");
+        if ((rc = read_status(plan, stream, st, "waiting for the ingestion plan"))) return rc;
+    }
+    if (st.err_word != ~0ull || st.num_segments < 1 || st.num_segments > m || st.total_lines < 0 || st.total_dir < 0) {
+        // no apply phase will run: the record is cleaned for the next batch here
+        if ((e = tns::ingest_status_reset(ds.d_status, stream)) != hipSuccess) return fail_hip(e, "resetting the ingestion status");
+    }
     if (st.err_word != ~0ull) {
         const int code = -(int)(st.err_word & 0xffu);
         const int64_t pos = (int64_t)(st.err_word >> 8);
@@ -380,11 +411,10 @@ int tns_add_edges_device(tns_plan* plan, int32_t instance, const int32_t* d_src,
     a.cap_lines = plan->d_edges.cap;
     a.cap_dir = std::min(plan->d_dir.cap, plan->d_dir_cum.cap);
 
-    e = tns::ingest_apply(a, st.num_segments, stream);
+    // The apply kernels are not waited for: the store changes in stream order, and an internal error they might
+    // raise (a pool too small, which the sizes above rule out) is reported by the next read of the status record.
+    e = tns::ingest_apply(a, st.num_segments, fast, stream);
     if (e != hipSuccess) return fail_hip(e, "launching the ingestion kernels");
-    tns::IngestStatus done;
-    if ((rc = read_status(plan, stream, done, "waiting for the ingestion kernels"))) return rc;
-    if (done.internal) return fail(TNS_EHIP, "ingestion kernels ran out of pool space (internal error)");
     plan->d_edges.used = lines_after;
     plan->d_dir.used = dir_after;
     plan->d_dir_cum.used = dir_after;
@@ -412,7 +442,8 @@ int tns_delete_edges(tns_plan* plan, int32_t instance, const int32_t* src, const
         int rc;
         if ((rc = ensure_device_store(plan, nullptr))) return rc;
         DeviceTemp<int32_t> d_src, d_eid;
-        hipError_t e = d_src.upload(src, m, nullptr);
+        hipError_t e = hipDeviceSynchronize();          // ingestion's last kernels may still be running on the caller's stream
+        if (e == hipSuccess) e = d_src.upload(src, m, nullptr);
         if (e == hipSuccess) e = d_eid.upload(eid, m, nullptr);
         if (e == hipSuccess)
             e = tns::ingest_delete_edges(plan->d_nodes.ptr, plan->d_dir.ptr, reinterpret_cast<uint32_t*>(plan->d_edges.ptr),
@@ -422,6 +453,7 @@ int tns_delete_edges(tns_plan* plan, int32_t instance, const int32_t* src, const
         tns::IngestStatus st;
         if ((rc = read_status(plan, nullptr, st, "waiting for the deletion kernel"))) return rc;
         plan->dev->totals[(size_t)instance].deleted += (int64_t)st.counter;
+        if (st.counter) plan->deleted_edges = true;
         if (num_deleted) *num_deleted = (int64_t)st.counter;
         return TNS_OK;
     }
@@ -432,6 +464,7 @@ int tns_delete_edges(tns_plan* plan, int32_t instance, const int32_t* src, const
         tns::Store& s = *plan->store;
         for (int64_t i = 0; i < m; ++i) hit += s.delete_edge(instance, src[i], eid[i]);
     }
+    if (hit) plan->deleted_edges = true;
     if (num_deleted) *num_deleted = hit;
     return TNS_OK;
 }
@@ -449,7 +482,8 @@ int tns_delete_nodes(tns_plan* plan, int32_t instance, const int32_t* nodes, int
         int rc;
         if ((rc = ensure_device_store(plan, nullptr))) return rc;
         DeviceTemp<int32_t> d_ids;
-        hipError_t e = d_ids.upload(nodes, m, nullptr);
+        hipError_t e = hipDeviceSynchronize();          // ingestion's last kernels may still be running on the caller's stream
+        if (e == hipSuccess) e = d_ids.upload(nodes, m, nullptr);
         if (e == hipSuccess)
             e = tns::ingest_delete_nodes(plan->d_nodes.ptr, (int64_t)instance * plan->cfg.num_nodes, d_ids.ptr, m, deleted, nullptr);
         if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
@@ -622,8 +656,10 @@ static int run_impl(tns_plan* plan, int64_t Q, const int32_t* d_targets, const f
     // One pass: sampling with the padding removal fused in.  With the edge data in host memory the reads
     // cross the host link and what counts is how many of them are in flight: the plain sampling kernel
     // keeps more waves resident than the fused one, so the two steps are run one after the other
-    // (C3, edge data on the host: 29.0 + 0.9 ms against 46.9 ms fused).
-    const bool fuse = want_cmp && !plan->d_edges.on_host;
+    // (C3, edge data on the host: 29.0 + 0.9 ms against 46.9 ms fused).  A store with deleted edges also takes the
+    // two steps: a block with deleted edges is scanned candidate by candidate, a hub query under the uniform policy
+    // can then take long, and in the fused kernel every later tile's bounded wait would be running meanwhile.
+    const bool fuse = want_cmp && !plan->d_edges.on_host && !plan->deleted_edges;
     if (fuse) {
         a.scan_ws = d_workspace;
         a.rowptr = d_rowptr;
@@ -841,7 +877,9 @@ int tns_stats(const tns_plan* plan, int32_t instance, tns_stats_t* out) {
         if (ds.d_status && n_nodes > 0) {
             DeviceGuard guard(plan->cfg.device);
             if (guard.error() != hipSuccess) return fail_hip(guard.error(), "selecting the plan's device");
-            hipError_t e = tns::ingest_max_list_len(plan->d_nodes.ptr, (int64_t)i0 * plan->cfg.num_nodes, n_nodes, ds.d_status, nullptr);
+            hipError_t e = hipDeviceSynchronize();      // ingestion's last kernels may still be running on the caller's stream
+            if (e == hipSuccess)
+                e = tns::ingest_max_list_len(plan->d_nodes.ptr, (int64_t)i0 * plan->cfg.num_nodes, n_nodes, ds.d_status, nullptr);
             tns::IngestStatus st{};
             if (e == hipSuccess) e = hipMemcpy(&st, ds.d_status, sizeof(st), hipMemcpyDeviceToHost);
             if (e != hipSuccess) return fail_hip(e, "reducing the list lengths");
@@ -907,7 +945,8 @@ int64_t tns_node_blocks(const tns_plan* plan, int32_t instance, int32_t node, in
         const int64_t nidx = (int64_t)instance * plan->cfg.num_nodes + node;
         tns::NodeLine nd;
         tns::NodeAux ax;
-        hipError_t e = hipMemcpy(&nd, plan->d_nodes.ptr + nidx, sizeof(nd), hipMemcpyDeviceToHost);
+        hipError_t e = hipDeviceSynchronize();          // ingestion's last kernels may still be running on the caller's stream
+        if (e == hipSuccess) e = hipMemcpy(&nd, plan->d_nodes.ptr + nidx, sizeof(nd), hipMemcpyDeviceToHost);
         if (e == hipSuccess) e = hipMemcpy(&ax, plan->dev->aux.ptr + nidx, sizeof(ax), hipMemcpyDeviceToHost);
         if (e != hipSuccess) return fail_hip(e, "reading a node entry");
         const int64_t n = nd.nblocks;
@@ -964,6 +1003,7 @@ int tns_destroy(tns_plan* plan) {
             plan->dev->aux.release();
             plan->dev->ws.release();
             if (plan->dev->d_status) (void)hipFree(plan->dev->d_status);
+            if (plan->dev->h_status) (void)hipHostFree(plan->dev->h_status);
         }
     }
     delete plan;

@@ -69,8 +69,15 @@ size_t ingest_workspace_bytes(int64_t m);
 // against what is stored, and compute what every node needs (edge lines, directory records).
 // Changes nothing in the store.  The host then reads *status, makes room, and runs phase 2.
 hipError_t ingest_plan(const IngestArgs& a, hipStream_t stream);
-// Phase 2: update node entries and block records, write the edges (num_segments as read from *status).
-hipError_t ingest_apply(const IngestArgs& a, int64_t num_segments, hipStream_t stream);
+// The same phase in five launches for batches of stream size (at most 2^18 edges, at most 2^24 nodes) that
+// arrive in time order: it sorts by source only and reports status->unsorted when the batch was not in time
+// order, in which case the caller runs ingest_plan instead.  Expects *status reset (ingest_apply leaves it so).
+bool ingest_fast_ok(int64_t m, int64_t num_nodes);
+hipError_t ingest_plan_fast(const IngestArgs& a, hipStream_t stream);
+// Phase 2: update node entries and block records, write the edges (num_segments as read from *status; `fast`:
+// the plan came from ingest_plan_fast).  Its first kernel resets *status for the next batch, except the sticky
+// `internal` word, which the next read of *status reports.
+hipError_t ingest_apply(const IngestArgs& a, int64_t num_segments, bool fast, hipStream_t stream);
 
 // Tombstone deletion on the device store: requests (node, edge id) [n]; status->counter receives the hits.
 hipError_t ingest_delete_edges(NodeLine* nodes, BlockRec* dir, uint32_t* lines, int64_t node_base, const int32_t* src,

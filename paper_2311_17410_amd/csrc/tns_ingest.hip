@@ -14,6 +14,7 @@
 // Nothing is changed before the host has seen the plan's status (errors reject the whole batch)
 // and made room in the pools.
 #include "tns_ingest.h"
+#include "tns_chain.h"
 
 #include <algorithm>
 
@@ -50,7 +51,6 @@ __global__ void __launch_bounds__(64) k_status_reset(IngestStatus* st) {
     if (threadIdx.x == 0) {
         st->err_word = ~0ull;
         st->unsorted = 0;
-        st->internal = 0;
         st->num_segments = 0;
         st->total_lines = 0;
         st->total_dir = 0;
@@ -308,60 +308,53 @@ __device__ __forceinline__ const BlockRec* tail_of(const IngestArgs& a, const No
     return &a.dir[(int64_t)nd.dir_line * kDirAlign + nd.nblocks - 1];
 }
 
-__global__ void __launch_bounds__(kThreads) k_plan(const IngestArgs a, const uint64_t* __restrict__ key, const uint32_t* __restrict__ val,
-                                                   const int32_t* __restrict__ seg_start, SegPlan* __restrict__ plan,
-                                                   int64_t* __restrict__ need_lines, int64_t* __restrict__ need_dir) {
-    const int64_t s = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    int64_t blocks = 0, slots = 0;
-    if (s < a.m) {
-        int64_t lines = 0, dirs = 0;
-        if (s < a.status->num_segments) {
-            const int32_t p0 = seg_start[s], p1 = seg_start[s + 1];
-            const int64_t mm = p1 - p0;
-            const uint32_t v = (uint32_t)(key[p0] >> 32);
-            SegPlan P{};
-            if ((uint64_t)v < (uint64_t)a.num_nodes) {      // out-of-range ids were reported by k_keys
-                const int64_t nidx = a.node_base + v;
-                const uint4 h = *reinterpret_cast<const uint4*>(&a.nodes[nidx]);
-                NodeLine nd;
-                nd.nblocks = (int32_t)h.x; nd.degree = (int32_t)h.y; nd.dir_line = h.z;
-                const NodeAux ax = a.aux[nidx];
-                int64_t room = 0;
-                if (nd.nblocks > 0) {
-                    const BlockRec tr = *tail_of(a, nd, nidx);
-                    if (a.ts[val[p0]] < tr.t_max) report(a.status, TNS_EORDER, a.m + (int64_t)v);
-                    room = ax.tail_cap - rec_size(tr);
-                    P.tail_slot = rec_off(tr) + rec_size(tr);
-                }
-                const int64_t take = room < mm ? (room > 0 ? room : 0) : mm;
-                const int64_t rest = mm - take;
-                P.take = (int32_t)take;
-                if (rest > 0) {
-                    int64_t cap;
-                    if (a.sizing == TNS_SIZING_STRAWMAN) cap = rest;
-                    else if (a.sizing == TNS_SIZING_FIXED) cap = a.tau;
-                    else cap = max(rest, min((int64_t)nd.degree + take, (int64_t)a.tau));   // b_v = min(deg(v), tau)
-                    cap = min(cap, kMaxBlockEdges);
-                    P.cap = (int32_t)cap;
-                    P.nbn = (int32_t)((rest + cap - 1) / cap);
-                    if (cap < kSlotsPerLine && ax.slab_line) {
-                        P.k0 = min(P.nbn, (kSlotsPerLine - ax.slab_used) / (int32_t)cap);
-                        P.slab_slot = (int64_t)(ax.slab_line - 1) * kSlotsPerLine + ax.slab_used;
-                    }
-                    lines = lines_of_blocks(P.cap, P.nbn, P.k0);
-                    const int64_t after = (int64_t)nd.nblocks + P.nbn;
-                    if (after > kInlineBlocks && after > ax.dir_cap) dirs = dir_run_for(after, ax.dir_cap);
-                    blocks = P.nbn;
-                    slots = (int64_t)P.nbn * cap;
-                }
-            }
-            plan[s] = P;
-        }
-        need_lines[s] = lines;
-        need_dir[s] = dirs;
+// What one segment (the batch's edges p0..p1 of one source node, sorted) needs: how many edges the tail block
+// still takes, the new blocks' capacity and number, the edge lines and directory records to reserve.
+__device__ __forceinline__ void plan_segment(const IngestArgs& a, const uint64_t* __restrict__ key, const uint32_t* __restrict__ val,
+                                             int32_t p0, int32_t p1, SegPlan& P, int64_t& lines, int64_t& dirs, int64_t& blocks,
+                                             int64_t& slots) {
+    const int64_t mm = p1 - p0;
+    const uint32_t v = (uint32_t)(key[p0] >> 32);
+    if ((uint64_t)v >= (uint64_t)a.num_nodes) return;      // out-of-range ids were reported with the keys
+    const int64_t nidx = a.node_base + v;
+    const uint4 h = *reinterpret_cast<const uint4*>(&a.nodes[nidx]);
+    NodeLine nd;
+    nd.nblocks = (int32_t)h.x; nd.degree = (int32_t)h.y; nd.dir_line = h.z;
+    const NodeAux ax = a.aux[nidx];
+    int64_t room = 0;
+    if (nd.nblocks > 0) {
+        const BlockRec tr = *tail_of(a, nd, nidx);
+        if (a.ts[val[p0]] < tr.t_max) report(a.status, TNS_EORDER, a.m + (int64_t)v);
+        room = ax.tail_cap - rec_size(tr);
+        P.tail_slot = rec_off(tr) + rec_size(tr);
     }
-    // totals: one pair of atomics per workgroup (atomics on one word serialise)
-    __shared__ int64_t s_blocks[kThreads / kWave], s_slots[kThreads / kWave];
+    const int64_t take = room < mm ? (room > 0 ? room : 0) : mm;
+    const int64_t rest = mm - take;
+    P.take = (int32_t)take;
+    if (rest > 0) {
+        int64_t cap;
+        if (a.sizing == TNS_SIZING_STRAWMAN) cap = rest;
+        else if (a.sizing == TNS_SIZING_FIXED) cap = a.tau;
+        else cap = max(rest, min((int64_t)nd.degree + take, (int64_t)a.tau));   // b_v = min(deg(v), tau)
+        cap = min(cap, kMaxBlockEdges);
+        P.cap = (int32_t)cap;
+        P.nbn = (int32_t)((rest + cap - 1) / cap);
+        if (cap < kSlotsPerLine && ax.slab_line) {
+            P.k0 = min(P.nbn, (kSlotsPerLine - ax.slab_used) / (int32_t)cap);
+            P.slab_slot = (int64_t)(ax.slab_line - 1) * kSlotsPerLine + ax.slab_used;
+        }
+        lines = lines_of_blocks(P.cap, P.nbn, P.k0);
+        const int64_t after = (int64_t)nd.nblocks + P.nbn;
+        if (after > kInlineBlocks && after > ax.dir_cap) dirs = dir_run_for(after, ax.dir_cap);
+        blocks = P.nbn;
+        slots = (int64_t)P.nbn * cap;
+    }
+}
+
+// totals of the new blocks and their capacities: one pair of atomics per workgroup (atomics on one word serialise)
+template <int WAVES = kThreads / kWave>
+__device__ __forceinline__ void add_block_totals(IngestStatus* st, int64_t blocks, int64_t slots) {
+    __shared__ int64_t s_blocks[WAVES], s_slots[WAVES];
     blocks = wave_sum64(blocks);
     slots = wave_sum64(slots);
     if ((threadIdx.x & (kWave - 1)) == 0) {
@@ -370,13 +363,34 @@ __global__ void __launch_bounds__(kThreads) k_plan(const IngestArgs a, const uin
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        blocks = s_blocks[0] + s_blocks[1] + s_blocks[2] + s_blocks[3];
-        slots = s_slots[0] + s_slots[1] + s_slots[2] + s_slots[3];
+        blocks = slots = 0;
+        for (int w = 0; w < WAVES; ++w) {
+            blocks += s_blocks[w];
+            slots += s_slots[w];
+        }
         if (blocks) {
-            atomicAdd(&a.status->new_blocks, (unsigned long long)blocks);
-            atomicAdd(&a.status->new_slots, (unsigned long long)slots);
+            atomicAdd(&st->new_blocks, (unsigned long long)blocks);
+            atomicAdd(&st->new_slots, (unsigned long long)slots);
         }
     }
+}
+
+__global__ void __launch_bounds__(kThreads) k_plan(const IngestArgs a, const uint64_t* __restrict__ key, const uint32_t* __restrict__ val,
+                                                   const int32_t* __restrict__ seg_start, SegPlan* __restrict__ plan,
+                                                   int64_t* __restrict__ need_lines, int64_t* __restrict__ need_dir) {
+    const int64_t s = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    int64_t blocks = 0, slots = 0;
+    if (s < a.m) {
+        int64_t lines = 0, dirs = 0;
+        if (s < a.status->num_segments) {
+            SegPlan P{};
+            plan_segment(a, key, val, seg_start[s], seg_start[s + 1], P, lines, dirs, blocks, slots);
+            plan[s] = P;
+        }
+        need_lines[s] = lines;
+        need_dir[s] = dirs;
+    }
+    add_block_totals(a.status, blocks, slots);
 }
 
 // One thread per segment: tail record, new block records, node entry, builder state.
@@ -468,9 +482,22 @@ __global__ void __launch_bounds__(kThreads) k_apply_nodes(const IngestArgs a, co
 __global__ void __launch_bounds__(kThreads) k_apply_edges(const IngestArgs a, const uint64_t* __restrict__ key,
                                                           const uint32_t* __restrict__ val, const int64_t* __restrict__ head_excl,
                                                           const int32_t* __restrict__ seg_start, const SegPlan* __restrict__ plan,
-                                                          const int64_t* __restrict__ lines_base) {
+                                                          const int64_t* __restrict__ lines_base, int reset_status) {
     const int64_t p = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (p >= a.m) return;
+    if (p == 0 && reset_status) {
+        // the host has read the plan; the record is made ready for the next batch here, so that the next
+        // plan needs no launch of its own for it (`internal` stays: it is reported by the next read-back)
+        IngestStatus* st = a.status;
+        st->err_word = ~0ull;
+        st->unsorted = 0;
+        st->num_segments = 0;
+        st->total_lines = 0;
+        st->total_dir = 0;
+        st->new_blocks = 0;
+        st->new_slots = 0;
+        st->counter = 0;
+    }
     const int64_t s = head_excl[p] + (is_head(key, p) ? 1 : 0) - 1;
     const SegPlan P = plan[s];
     const int64_t r = p - seg_start[s];
@@ -488,6 +515,344 @@ __global__ void __launch_bounds__(kThreads) k_apply_edges(const IngestArgs a, co
     a.lines[w] = __float_as_uint(a.ts[e]);
     a.lines[w + 1] = (uint32_t)a.dst[e];
     a.lines[w + 2] = (uint32_t)(a.eid ? a.eid[e] : (int32_t)(a.eid_base + (int64_t)e));
+}
+
+// ---- short pipeline for stream-sized batches -------------------------------------------------
+//
+// A batch of the size streams are ingested in (the paper's 100 K edges) spends its time in launches,
+// not in memory traffic, so the planning phase above (about 40 dependent launches) is cut to five
+// for batches that fit kFastMaxBatch and arrive in time order, the usual case for a stream:
+//   k_fast_keys      validation, keys, and every tile's histogram of the first digit;
+//   k_fast_scatter   x 2: stable radix pass over one half of the source id's bits.  Every tile adds
+//                    up the histograms of the tiles before it by itself (at most kFastMaxTiles rows, read
+//                    from the L2), so a pass needs no separate scan launch and no tile waits for another;
+//                    the first pass also counts the second digit per destination tile for the second pass;
+//   k_fast_segments  segment heads, their numbering (chained scan over tiles) and the segment starts;
+//   k_fast_plan      the per-segment plan and the pool offsets (two chained scans) in one launch.
+// Time order is assumed, not known: k_fast_keys sets `unsorted` as the general pipeline does, and
+// the host, which reads the status before anything is changed, then runs the general pipeline instead.
+constexpr int kFastItems = 16;                          // keys per thread and tile
+constexpr int kFastTile = kThreads * kFastItems;        // 4096 keys per tile
+constexpr int kScatThreads = 512;                       // the radix passes: 8 waves x 8 keys per lane on the same tiles
+constexpr int kScatItems = kFastTile / kScatThreads;
+constexpr int kFastMaxTiles = 64;
+constexpr int64_t kFastMaxBatch = (int64_t)kFastTile * kFastMaxTiles;   // 2^18 edges
+constexpr int kFastMaxBits = 12;                        // bits per digit: two digits cover 2^24 nodes
+constexpr int kSegItems = 4;                            // positions per thread in k_fast_segments
+constexpr int kPlanThreads = 1024;                      // k_fast_plan: one segment per thread, 1024 per tile
+constexpr uint32_t kInternalScan = 8u;                  // IngestStatus::internal: a chained scan's bounded wait ran out
+
+
+template <int WAVES = kThreads / kWave>
+__device__ __forceinline__ int64_t block_exclusive_scan(int64_t v, int64_t* s_wave /* [WAVES] */, int64_t& total) {
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    int64_t inc = v;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int64_t u = (int64_t)__shfl_up((long long)inc, d, kWave);
+        if (lane >= d) inc += u;
+    }
+    if (lane == kWave - 1) s_wave[wave] = inc;
+    __syncthreads();
+    int64_t off = 0;
+    total = 0;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) {
+        const int64_t t = s_wave[w];
+        if (w < wave) off += t;
+        total += t;
+    }
+    __syncthreads();
+    return off + inc - v;
+}
+
+// Tile index in launch order, and the sum of the totals of the tiles before it: one chained-scan step of a
+// workgroup.  `total` is the tile's own sum; the inclusive prefix is published for the tiles after it.
+// Called by one whole wave; lane 0 holds the result.  A bounded wait that runs out marks the scan's own error
+// word (later tiles and kernels look at it) and the status record the host reads.
+__device__ __forceinline__ int64_t chain_wave(ScanWorkspace* ws, IngestStatus* st, int64_t tile, int64_t total, int lane) {
+    if (lane == 0 && tile > 0)
+        __hip_atomic_store(&ws->status[tile], kStTotal | (uint64_t)total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int64_t excl = tile > 0 ? lookback_exclusive(ws, &ws->error, tile, lane) : 0;
+    if (lane == 0) {
+        __hip_atomic_store(&ws->status[tile], kStPrefix | (uint64_t)(excl + total), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (__hip_atomic_load(&ws->error, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) atomicOr(&st->internal, kInternalScan);
+    }
+    return excl;
+}
+
+__global__ void __launch_bounds__(kThreads) k_fast_keys(const IngestArgs a, uint64_t* __restrict__ key, uint32_t* __restrict__ val,
+                                                        uint32_t* __restrict__ hist1, uint32_t* __restrict__ hist2, int bits,
+                                                        ScanWorkspace* seg_scan, ScanWorkspace* lines_scan, ScanWorkspace* dir_scan,
+                                                        int seg_tiles, int plan_tiles) {
+    extern __shared__ uint32_t s_hist[];     // [bins]
+    const int bins = 1 << bits;
+    for (int b = threadIdx.x; b < bins; b += kThreads) s_hist[b] = 0;
+    __syncthreads();
+    const int64_t base = (int64_t)blockIdx.x * kFastTile;
+    int32_t v_[kFastItems], e_[kFastItems];
+    float t_[kFastItems], tp_[kFastItems];
+#pragma unroll
+    for (int j = 0; j < kFastItems; ++j) {       // all loads first, clamped to the batch
+        const int64_t i = min(base + (int64_t)j * kThreads + threadIdx.x, a.m - 1);
+        v_[j] = a.src[i];
+        t_[j] = a.ts[i];
+        tp_[j] = a.ts[i > 0 ? i - 1 : 0];
+        e_[j] = a.eid ? a.eid[i] : 0;
+    }
+#pragma unroll
+    for (int j = 0; j < kFastItems; ++j) {
+        const int64_t i = base + (int64_t)j * kThreads + threadIdx.x;
+        if (i >= a.m) continue;
+        const int32_t v = v_[j];
+        const float t = t_[j];
+        if ((uint64_t)(uint32_t)v >= (uint64_t)a.num_nodes) report(a.status, TNS_ERANGE, i);
+        else if (t != t) report(a.status, TNS_EORDER, i);
+        else if (e_[j] < 0) report(a.status, TNS_EINVAL, i);
+        if (i > 0 && tp_[j] > t) atomicOr(&a.status->unsorted, 1u);
+        uint32_t u = t == 0.0f ? 0u : __float_as_uint(t);
+        u ^= (u >> 31) ? 0xffffffffu : 0x80000000u;
+        key[i] = ((uint64_t)(uint32_t)v << 32) | u;
+        val[i] = (uint32_t)i;
+        atomicAdd(&s_hist[(uint32_t)v & (uint32_t)(bins - 1)], 1u);
+    }
+    __syncthreads();
+    uint32_t* row1 = hist1 + (size_t)blockIdx.x * bins;
+    uint32_t* row2 = hist2 + (size_t)blockIdx.x * bins;
+    for (int b = threadIdx.x; b < bins; b += kThreads) {
+        row1[b] = s_hist[b];
+        row2[b] = 0;                      // filled by the first scatter pass
+    }
+    if (blockIdx.x == 0) {
+        // tickets, error words and tile states of the three chained scans that follow
+        for (int i = threadIdx.x; i < seg_tiles + 1; i += kThreads) seg_scan->status[i] = 0;
+        for (int i = threadIdx.x; i < plan_tiles + 1; i += kThreads) {
+            lines_scan->status[i] = 0;
+            dir_scan->status[i] = 0;
+        }
+        if (threadIdx.x == 0) {
+            seg_scan->ticket = 0; seg_scan->error = 0;
+            lines_scan->ticket = 0; lines_scan->error = 0;
+            dir_scan->ticket = 0; dir_scan->error = 0;
+        }
+    }
+}
+
+// One stable radix pass over `bits` bits of the key starting at `shift`.  A wave owns kScatItems * 64
+// consecutive keys of the tile and takes them 64 at a time in order, so "earlier in the tile" is
+// (wave, item, lane) order; a key's rank among equal digits is the count of its wave so far plus its rank
+// among the lanes of the current item (ballots over the digit's bits).
+__global__ void __launch_bounds__(kScatThreads) k_fast_scatter(const uint64_t* __restrict__ kin, const uint32_t* __restrict__ vin,
+                                                           uint64_t* __restrict__ kout, uint32_t* __restrict__ vout, int64_t m,
+                                                           int shift, int bits, int tiles, const uint32_t* __restrict__ hist,
+                                                           uint32_t* __restrict__ hist_next, int shift_next) {
+    extern __shared__ uint32_t smem[];
+    const int bins = 1 << bits;
+    uint32_t* s_off = smem;                     // [bins]  position of the tile's first key of each digit
+    uint32_t* s_cnt = smem + bins;              // [waves][bins]
+    __shared__ int64_t s_wave[kScatThreads / kWave];
+    const int t = threadIdx.x, lane = t & (kWave - 1), wave = t / kWave;
+    const int tile = blockIdx.x;
+    const uint32_t mask = (uint32_t)(bins - 1);
+
+    // keys with this digit in earlier tiles, and in all tiles: thread t owns `per` consecutive digits and reads
+    // their counts of every tile (16-byte loads when it owns four or more)
+    const int per = bins >= kScatThreads ? bins / kScatThreads : 1;
+    int64_t mine = 0;
+    if (per >= 4) {
+        for (int k = 0; k < per; k += 4) {
+            const int b = t * per + k;
+            uint4 before = make_uint4(0, 0, 0, 0), all = make_uint4(0, 0, 0, 0);
+            // eight rows are requested before the first is added up: the rows come from the L2 and a thread
+            // that waited for each in turn would spend the whole pass here
+            for (int r0 = 0; r0 < tiles; r0 += 8) {
+                uint4 c[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int r = min(r0 + u, tiles - 1);
+                    c[u] = *reinterpret_cast<const uint4*>(hist + (size_t)r * bins + b);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int r = r0 + u;
+                    if (r < tiles) { all.x += c[u].x; all.y += c[u].y; all.z += c[u].z; all.w += c[u].w; }
+                    if (r < tile) { before.x += c[u].x; before.y += c[u].y; before.z += c[u].z; before.w += c[u].w; }
+                }
+            }
+            s_off[b] = before.x; s_off[b + 1] = before.y; s_off[b + 2] = before.z; s_off[b + 3] = before.w;
+            s_cnt[b] = all.x; s_cnt[b + 1] = all.y; s_cnt[b + 2] = all.z; s_cnt[b + 3] = all.w;   // parked in the first
+            mine += (int64_t)all.x + all.y + all.z + all.w;                                        // wave's row for now
+        }
+    } else {
+        for (int k = 0; k < per; ++k) {
+            const int b = t * per + k;
+            if (b >= bins) break;
+            uint32_t before = 0, all = 0;
+            for (int r0 = 0; r0 < tiles; r0 += 8) {
+                uint32_t c[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) c[u] = hist[(size_t)min(r0 + u, tiles - 1) * bins + b];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    if (r0 + u < tiles) all += c[u];
+                    if (r0 + u < tile) before += c[u];
+                }
+            }
+            s_off[b] = before;
+            s_cnt[b] = all;
+            mine += all;
+        }
+    }
+    int64_t total;
+    int64_t run = block_exclusive_scan<kScatThreads / kWave>(mine, s_wave, total);       // keys with a smaller digit than this thread's first
+    for (int k = 0; k < per; ++k) {
+        const int b = t * per + k;
+        if (b >= bins) break;
+        const uint32_t all = s_cnt[b];
+        s_off[b] += (uint32_t)run;
+        run += all;
+    }
+    __syncthreads();
+    for (int i = t; i < bins * (kScatThreads / kWave); i += kScatThreads) s_cnt[i] = 0;
+    __syncthreads();
+
+    const int64_t wbase = (int64_t)tile * kFastTile + (int64_t)wave * (kScatItems * kWave);
+    uint64_t k_[kScatItems];
+    uint32_t v_[kScatItems], r_[kScatItems];
+    uint32_t* my_cnt = s_cnt + (size_t)wave * bins;
+#pragma unroll
+    for (int j = 0; j < kScatItems; ++j) {       // all loads of the tile first
+        const int64_t i = min(wbase + (int64_t)j * kWave + lane, m - 1);   // clamped: no load sits in a branch
+        k_[j] = kin[i];
+        v_[j] = vin[i];
+    }
+#pragma unroll
+    for (int j = 0; j < kScatItems; ++j) {
+        const int64_t i = wbase + (int64_t)j * kWave + lane;
+        const bool valid = i < m;
+        const uint32_t d = (uint32_t)(k_[j] >> shift) & mask;
+        uint64_t same = __ballot(valid);
+        for (int b = 0; b < bits; ++b) {
+            const bool bit = (d >> b) & 1u;
+            const uint64_t bal = __ballot(bit);
+            same &= bit ? bal : ~bal;
+        }
+        const int leader = same ? __builtin_ctzll(same) : 0;
+        uint32_t prev = 0;
+        if (valid && lane == leader) {
+            prev = my_cnt[d];
+            my_cnt[d] = prev + (uint32_t)__popcll(same);
+        }
+        prev = (uint32_t)__shfl((int)prev, leader, kWave);
+        r_[j] = prev + (uint32_t)__popcll(same & ((1ull << lane) - 1ull));
+    }
+    __syncthreads();
+    // a wave's keys of a digit follow those of the earlier waves
+    for (int b = t; b < bins; b += kScatThreads) {
+        uint32_t acc = 0;
+#pragma unroll
+        for (int w = 0; w < kScatThreads / kWave; ++w) {
+            const uint32_t c = s_cnt[(size_t)w * bins + b];
+            s_cnt[(size_t)w * bins + b] = acc;
+            acc += c;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kScatItems; ++j) {
+        const int64_t i = wbase + (int64_t)j * kWave + lane;
+        if (i >= m) continue;
+        const uint32_t d = (uint32_t)(k_[j] >> shift) & mask;
+        const uint32_t pos = s_off[d] + my_cnt[d] + r_[j];
+        if ((int64_t)pos < m) {                 // always true for consistent histograms; keeps a bad one in bounds
+            kout[pos] = k_[j];
+            vout[pos] = v_[j];
+            if (hist_next) atomicAdd(&hist_next[(size_t)(pos / kFastTile) * bins + ((uint32_t)(k_[j] >> shift_next) & mask)], 1u);
+        }
+    }
+}
+
+// Sorted keys -> segment heads, head_excl[p] = number of heads before position p, seg_start[s] = first
+// position of segment s (and m after the last), status->num_segments.
+__global__ void __launch_bounds__(kThreads) k_fast_segments(const uint64_t* __restrict__ key, int64_t m, int64_t* __restrict__ head_excl,
+                                                            int32_t* __restrict__ seg_start, ScanWorkspace* ws, IngestStatus* st) {
+    __shared__ int64_t s_wave[kThreads / kWave];
+    __shared__ int64_t s_tile, s_excl;
+    if (threadIdx.x == 0) s_tile = (int64_t)atomicAdd(&ws->ticket, 1u);
+    __syncthreads();
+    const int64_t tile = s_tile;
+    const int64_t p0 = (tile * kThreads + threadIdx.x) * kSegItems;
+    int h[kSegItems];
+    int64_t mine = 0;
+#pragma unroll
+    for (int j = 0; j < kSegItems; ++j) {
+        const int64_t p = p0 + j;
+        h[j] = (p < m && is_head(key, p)) ? 1 : 0;
+        mine += h[j];
+    }
+    int64_t total;
+    int64_t run = block_exclusive_scan(mine, s_wave, total);
+    if (threadIdx.x < kWave) {
+        const int64_t excl = chain_wave(ws, st, tile, total, threadIdx.x);
+        if (threadIdx.x == 0) s_excl = excl;
+    }
+    __syncthreads();
+    run += s_excl;
+#pragma unroll
+    for (int j = 0; j < kSegItems; ++j) {
+        const int64_t p = p0 + j;
+        if (p >= m) break;
+        head_excl[p] = run;
+        if (h[j]) seg_start[run] = (int32_t)p;
+        run += h[j];
+        if (p == m - 1) {
+            seg_start[run] = (int32_t)m;
+            st->num_segments = run;
+        }
+    }
+}
+
+// The per-segment plan and, in the same launch, every segment's offset into the edge-line and directory pools.
+__global__ void __launch_bounds__(kPlanThreads) k_fast_plan(const IngestArgs a, const uint64_t* __restrict__ key,
+                                                            const uint32_t* __restrict__ val, const int32_t* __restrict__ seg_start,
+                                                            SegPlan* __restrict__ plan, int64_t* __restrict__ lines_base,
+                                                            int64_t* __restrict__ dir_base, const ScanWorkspace* seg_scan,
+                                                            ScanWorkspace* lines_scan, ScanWorkspace* dir_scan, int plan_tiles) {
+    constexpr int kWaves = kPlanThreads / kWave;
+    __shared__ int64_t s_wave[kWaves];
+    __shared__ int64_t s_tile, s_excl_lines, s_excl_dir;
+    if (threadIdx.x == 0) s_tile = (int64_t)atomicAdd(&lines_scan->ticket, 1u);
+    __syncthreads();
+    const int64_t tile = s_tile;
+    // a time-out of the segment numbering leaves seg_start incomplete: nothing may be read through it
+    const bool ok = seg_scan->error == 0;
+    const int64_t nseg = ok ? a.status->num_segments : 0;
+    const int64_t s = tile * kPlanThreads + threadIdx.x;
+    int64_t lines = 0, dirs = 0, blocks = 0, slots = 0;
+    if (s < nseg) {
+        SegPlan P{};
+        plan_segment(a, key, val, seg_start[s], seg_start[s + 1], P, lines, dirs, blocks, slots);
+        plan[s] = P;
+    }
+    int64_t tot_lines, tot_dir;
+    const int64_t in_lines = block_exclusive_scan<kWaves>(lines, s_wave, tot_lines);
+    const int64_t in_dir = block_exclusive_scan<kWaves>(dirs, s_wave, tot_dir);
+    // the two look-backs run side by side in the first two waves
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    if (wave < 2) {
+        const int64_t excl = chain_wave(wave == 0 ? lines_scan : dir_scan, a.status, tile, wave == 0 ? tot_lines : tot_dir, lane);
+        if (lane == 0) *(wave == 0 ? &s_excl_lines : &s_excl_dir) = excl;
+    }
+    __syncthreads();
+    if (s < a.m) {
+        lines_base[s] = s_excl_lines + in_lines;
+        dir_base[s] = s_excl_dir + in_dir;
+    }
+    if (tile == plan_tiles - 1 && threadIdx.x == 0) {
+        a.status->total_lines = s_excl_lines + tot_lines;
+        a.status->total_dir = s_excl_dir + tot_dir;
+    }
+    add_block_totals<kWaves>(a.status, blocks, slots);
 }
 
 // ---- deletion, statistics ------------------------------------------------------------------
@@ -551,6 +916,10 @@ struct Carve {
     SegPlan* plan;
     int64_t chunk;
     int nblk;
+    // short pipeline (batches of at most kFastMaxBatch edges)
+    uint32_t* tile_hist[2];        // [tiles][bins] per radix pass
+    ScanWorkspace *seg_scan, *lines_scan, *dir_scan;
+    int fast_tiles, seg_tiles, plan_tiles;
     size_t bytes;
 };
 
@@ -574,6 +943,16 @@ Carve carve(void* ws, int64_t m) {
     c.sums = reinterpret_cast<int64_t*>(take(((mm + kScanTile - 1) / kScanTile + 1) * 8));
     c.seg_start = reinterpret_cast<int32_t*>(take((mm + 1) * 4));
     c.plan = reinterpret_cast<SegPlan*>(take(mm * sizeof(SegPlan)));
+    if (m <= kFastMaxBatch) {
+        c.fast_tiles = (int)((mm + kFastTile - 1) / kFastTile);
+        c.seg_tiles = (int)((mm + kThreads * kSegItems - 1) / (kThreads * kSegItems));
+        c.plan_tiles = (int)((mm + kPlanThreads - 1) / kPlanThreads);
+        for (int p2 = 0; p2 < 2; ++p2)
+            c.tile_hist[p2] = reinterpret_cast<uint32_t*>(take((size_t)c.fast_tiles * (size_t(1) << kFastMaxBits) * 4));
+        c.seg_scan = reinterpret_cast<ScanWorkspace*>(take(sizeof(ScanWorkspace) + (size_t)(c.seg_tiles + 1) * 8));
+        c.lines_scan = reinterpret_cast<ScanWorkspace*>(take(sizeof(ScanWorkspace) + (size_t)(c.plan_tiles + 1) * 8));
+        c.dir_scan = reinterpret_cast<ScanWorkspace*>(take(sizeof(ScanWorkspace) + (size_t)(c.plan_tiles + 1) * 8));
+    }
     c.bytes = o;
     return c;
 }
@@ -628,14 +1007,44 @@ hipError_t ingest_plan(const IngestArgs& a, hipStream_t stream) {
     return exclusive_scan64(c.dir_base, c.dir_base, m, c.sums, &a.status->total_dir, stream);
 }
 
-hipError_t ingest_apply(const IngestArgs& a, int64_t num_segments, hipStream_t stream) {
+// Bits per digit of the short pipeline's two radix passes, or 0 if the batch does not qualify.
+int fast_digit_bits(int64_t m, int64_t num_nodes) {
+    if (m > kFastMaxBatch) return 0;
+    int bits = 0;
+    while (bits < 32 && (int64_t(1) << bits) < num_nodes) ++bits;
+    if (bits > 2 * kFastMaxBits) return 0;
+    return std::max(1, (bits + 1) / 2);
+}
+
+bool ingest_fast_ok(int64_t m, int64_t num_nodes) { return fast_digit_bits(m, num_nodes) > 0; }
+
+hipError_t ingest_plan_fast(const IngestArgs& a, hipStream_t stream) {
+    const int bits = fast_digit_bits(a.m, a.num_nodes);
+    if (a.m <= 0 || bits <= 0) return hipErrorInvalidValue;
+    const Carve c = carve(a.workspace, a.m);
+    const int bins = 1 << bits;
+    hipLaunchKernelGGL(k_fast_keys, dim3((unsigned)c.fast_tiles), dim3(kThreads), (size_t)bins * 4, stream, a, c.keyA, c.valA,
+                       c.tile_hist[0], c.tile_hist[1], bits, c.seg_scan, c.lines_scan, c.dir_scan, c.seg_tiles, c.plan_tiles);
+    const size_t lds = (size_t)bins * 4 * (1 + kScatThreads / kWave);
+    hipLaunchKernelGGL(k_fast_scatter, dim3((unsigned)c.fast_tiles), dim3(kScatThreads), lds, stream, c.keyA, c.valA, c.keyB, c.valB, a.m,
+                       32, bits, c.fast_tiles, c.tile_hist[0], c.tile_hist[1], 32 + bits);
+    hipLaunchKernelGGL(k_fast_scatter, dim3((unsigned)c.fast_tiles), dim3(kScatThreads), lds, stream, c.keyB, c.valB, c.keyA, c.valA, a.m,
+                       32 + bits, bits, c.fast_tiles, c.tile_hist[1], (uint32_t*)nullptr, 0);
+    hipLaunchKernelGGL(k_fast_segments, dim3((unsigned)c.seg_tiles), dim3(kThreads), 0, stream, c.keyA, a.m, c.head_excl, c.seg_start,
+                       c.seg_scan, a.status);
+    hipLaunchKernelGGL(k_fast_plan, dim3((unsigned)c.plan_tiles), dim3(kPlanThreads), 0, stream, a, c.keyA, c.valA, c.seg_start, c.plan,
+                       c.lines_base, c.dir_base, c.seg_scan, c.lines_scan, c.dir_scan, c.plan_tiles);
+    return hipGetLastError();
+}
+
+hipError_t ingest_apply(const IngestArgs& a, int64_t num_segments, bool fast, hipStream_t stream) {
     if (a.m <= 0 || num_segments <= 0 || num_segments > a.m) return hipErrorInvalidValue;
     const Carve c = carve(a.workspace, a.m);
-    const bool in_b = (src_passes(a.num_nodes) & 1) != 0;
+    const bool in_b = !fast && (src_passes(a.num_nodes) & 1) != 0;
     const uint64_t* key = in_b ? c.keyB : c.keyA;
     const uint32_t* val = in_b ? c.valB : c.valA;
     hipLaunchKernelGGL(k_apply_edges, dim3(grid_for(a.m)), dim3(kThreads), 0, stream, a, key, val, c.head_excl, c.seg_start, c.plan,
-                       c.lines_base);
+                       c.lines_base, 1);
     hipLaunchKernelGGL(k_apply_nodes, dim3(grid_for(num_segments)), dim3(kThreads), 0, stream, a, val, c.seg_start, c.plan,
                        c.lines_base, c.dir_base, num_segments, key);
     return hipGetLastError();

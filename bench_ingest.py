@@ -74,9 +74,13 @@ def main() -> int:
     cpu = None
     if args.cpu_seconds > 0:
         bs = oracle.BlockStore(st.num_nodes, wl.tau, 0)
-        k = min(st.n, max(m, int(args.cpu_seconds * 4e6) // m * m))
         t0 = time.perf_counter()
-        bs.add_stream(st.src[:k], st.dst[:k], st.ts[:k], m)
+        k = 0
+        for lo, hi in bounds:            # batch by batch, so that the time budget holds at every batch size
+            bs.add_batch(st.src[lo:hi], st.dst[lo:hi], st.ts[lo:hi])
+            k = hi
+            if time.perf_counter() - t0 > args.cpu_seconds:
+                break
         cpu_s = time.perf_counter() - t0
         cpu = {"value": k / cpu_s, "unit": "edges/s", "cores": 1, "kind": "oracle",
                "sample": f"the first {k} edges of the same stream in the same batches, {cpu_s:.1f} s"}

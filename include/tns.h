@@ -139,8 +139,12 @@ TNS_API int tns_add_edges(tns_plan *plan, int32_t instance, const int32_t *src, 
  * edges remain, to new blocks sized by the same rule as tns_add_edges; block capacities, sizes and
  * time ranges per node are identical to the host builder's, only where the blocks lie in the edge
  * array differs.  Same status codes; a rejected batch changes nothing.  The call grows the
- * device pools when needed (it may allocate), waits for the stream, and returns when the batch
- * is stored: a later tns_run on any stream sees it.  No tns_commit is needed.
+ * device pools when needed (it may allocate) and waits for the stream once, to read the batch's
+ * plan; it returns with the kernels that write the batch queued on hip_stream: a later tns_run
+ * on that stream sees the batch, work on another stream has to wait for hip_stream first.  No
+ * tns_commit is needed.  An error of the library itself (TNS_EHIP: a pool found too small by those
+ * kernels, a bounded wait that ran out) is reported by the next call that reads the builder's
+ * status, at the latest the next tns_add_edges_device.
  */
 TNS_API int tns_add_edges_device(tns_plan *plan, int32_t instance, const int32_t *d_src, const int32_t *d_dst,
                                  const float *d_ts, const int32_t *d_eid, int64_t m, void *hip_stream);

@@ -205,6 +205,10 @@ TNS_API int tns_workspace(const tns_plan *plan, int64_t Q, size_t *bytes);
  *                     neighbour id, edge id and timestamp of one sampled edge (recent: newest
  *                     first; uniform: draw order); slots >= count hold -1, -1, 0.0f
  *   d_out_count[Q]    number of filled slots per query, min(fanout, candidates)
+ *                     All four padded outputs may be NULL together when the padding is removed in
+ *                     the same kernel (d_rowptr given, edge data in device memory, no deleted
+ *                     edges; TNS_EINVAL otherwise): the padded rows are then never written, only
+ *                     the dense result is (the counts are d_rowptr[q+1] - d_rowptr[q])
  *   d_rowptr[Q+1], d_cmp_nbr/eid/ts[sum of counts]
  *                     padding removed: exclusive prefix sum of counts and the filled slots in
  *                     (query, slot) order.  d_rowptr NULL (and the other three NULL) skips

@@ -372,7 +372,7 @@ class Plan:
         with torch.cuda.device(self.device):
             stream = torch.cuda.current_stream().cuda_stream
             tns_run(self._h, Q, p(targets), p(t_start), p(t_end), p(inst_rowptr), query_id_base,
-                    p(out["nbr"]), p(out["eid"]), p(out["ts"]), p(out["count"]),
+                    p(out.get("nbr")), p(out.get("eid")), p(out.get("ts")), p(out.get("count")),
                     p(out.get("rowptr")), p(out.get("cmp_nbr")), p(out.get("cmp_eid")), p(out.get("cmp_ts")),
                     p(out.get("workspace")), 0 if out.get("workspace") is None else out["workspace"].numel(), stream)
         return out

@@ -634,9 +634,11 @@ static int run_impl(tns_plan* plan, int64_t Q, const int32_t* d_targets, const f
     tns::SampleArgs a;
     int rc = fill_sample_args(plan, Q, d_targets, d_t_start, d_t_end, d_inst_rowptr, query_id_base, a);
     if (rc) return rc;
-    if (Q > 0 && (!d_out_nbr || !d_out_eid || !d_out_ts || !d_out_count)) return fail(TNS_EINVAL, "null output pointer");
     // compaction is requested by d_rowptr; with Q == 0 the dense arrays are empty and may be null
     const bool want_cmp = d_rowptr != nullptr;
+    // dense-only run: all four padded outputs null, the padded rows are never written
+    const bool dense_only = want_cmp && !d_out_nbr && !d_out_eid && !d_out_ts && !d_out_count;
+    if (Q > 0 && !dense_only && (!d_out_nbr || !d_out_eid || !d_out_ts || !d_out_count)) return fail(TNS_EINVAL, "null output pointer");
     if (!want_cmp && (d_cmp_nbr || d_cmp_eid || d_cmp_ts)) return fail(TNS_EINVAL, "pass all four compaction outputs or none");
 
     DeviceGuard guard(plan->cfg.device);
@@ -660,6 +662,8 @@ static int run_impl(tns_plan* plan, int64_t Q, const int32_t* d_targets, const f
     // two steps: a block with deleted edges is scanned candidate by candidate, a hub query under the uniform policy
     // can then take long, and in the fused kernel every later tile's bounded wait would be running meanwhile.
     const bool fuse = want_cmp && !plan->d_edges.on_host && !plan->deleted_edges;
+    if (dense_only && !fuse)
+        return fail(TNS_EINVAL, "this plan removes the padding in a step of its own (edge data on the host, or deleted edges) and needs the padded outputs");
     if (fuse) {
         a.scan_ws = d_workspace;
         a.rowptr = d_rowptr;

@@ -294,6 +294,7 @@ __device__ __forceinline__ void gather_load(GatherRegs& g, const SampleArgs& p, 
 // padded rows: slots of queries below Q, empty slots get the sentinels
 __device__ __forceinline__ void store_padded(const GatherRegs& g, const SampleArgs& p, uint32_t f_magic, int lane,
                                              int32_t it0, int64_t q0, int64_t Q) {
+    if (!p.out_nbr) return;      // dense-only run: the padded rows are not materialised
     const int32_t f = p.fanout;
     const int64_t out0 = q0 * f;
 #pragma unroll

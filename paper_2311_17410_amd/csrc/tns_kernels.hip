@@ -408,7 +408,7 @@ __global__ void __launch_bounds__(FUSED ? 1024 : 256, FUSED ? 4 : 6) tns_sample_
             store_padded(g, p, f_magic, lane, it0, q0, Q);
         }
     }
-    if (q < Q) __builtin_nontemporal_store(k, &p.out_count[q]);
+    if (q < Q && p.out_count) __builtin_nontemporal_store(k, &p.out_count[q]);
 }
 
 // ---- padding removal -------------------------------------------------------------------

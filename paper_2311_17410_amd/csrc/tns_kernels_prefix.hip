@@ -628,7 +628,7 @@ __global__ void __launch_bounds__(1024) tns_sample_prefix_kernel(const SampleArg
             }
         }
     }
-    if (q < Q) __builtin_nontemporal_store(k, &p.out_count[q]);
+    if (q < Q && p.out_count) __builtin_nontemporal_store(k, &p.out_count[q]);
 }
 
 inline uint32_t magic_of(int32_t f) { return f <= 1 ? 0u : (uint32_t)(((uint64_t(1) << 32) + (uint64_t)f - 1) / (uint64_t)f); }

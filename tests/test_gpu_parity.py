@@ -408,6 +408,40 @@ def test_host_placement_gives_the_same_results(B, oracle_lib, policy):
         plan.close()
 
 
+@pytest.mark.parametrize("policy", [0, 1])
+def test_dense_only_run(B, oracle_lib, policy):
+    """tns_run with the four padded outputs NULL writes the dense result only: rowptr and the dense arrays equal the
+    oracle's compaction of its padded result; a plan that removes the padding in a step of its own refuses the form."""
+    import torch
+    wl = W.c2()
+    targets, t_start, t_end, _ = wl.queries(window_frac=0.25)
+    plan = build_plan(B, wl, policy, 0, seed=3)
+    dev = torch.device("cuda", plan.device)
+    Q, f = len(targets), wl.fanout
+    d = [torch.from_numpy(a).to(dev) for a in (targets, t_start, t_end)]
+    full = plan.alloc_outputs(Q, compact=True)
+    out = {k: full[k] for k in ("rowptr", "cmp_nbr", "cmp_eid", "cmp_ts", "workspace")}
+    plan.run(d[0], d[1], d[2], out=out)
+    torch.cuda.synchronize()
+    assert not plan.status(out["workspace"])
+    ref = oracle_sample(oracle_lib, wl, targets, t_start, t_end, None, f, policy, 0, 3, threads=16)
+    rowptr, cn, ce, ct = oracle_lib.compact(ref)
+    total = int(rowptr[-1])
+    assert np.array_equal(out["rowptr"].cpu().numpy(), rowptr)
+    assert np.array_equal(out["cmp_eid"][:total].cpu().numpy(), ce) and np.array_equal(out["cmp_nbr"][:total].cpu().numpy(), cn)
+    assert np.array_equal(out["cmp_ts"][:total].cpu().numpy().view(np.int32), ct.view(np.int32))
+    # without the dense outputs there is nothing left to write: refused
+    with pytest.raises(B.TnsError):
+        plan.run(d[0], d[1], d[2], out={}, compact=False)
+    # a plan with deleted edges removes the padding in a second step, which reads the padded rows
+    st = wl.streams[0]
+    assert B.tns_delete_edges(plan.handle, 0, st.src[:1], np.array([0], np.int32)) == 1
+    plan.commit()
+    with pytest.raises(B.TnsError):
+        plan.run(d[0], d[1], d[2], out=out)
+    plan.close()
+
+
 def test_c3_zipf_hub(B, oracle_lib):
     progress("generating C3")
     _check_config(B, oracle_lib, W.c3())

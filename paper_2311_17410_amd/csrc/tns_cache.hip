@@ -97,27 +97,30 @@ __global__ void __launch_bounds__(256) k_lookup(CacheState c, int policy, int64_
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // out[b] = cached row or row of the backing store; VEC floats per thread, rows stay coalesced
+// The slot comes from the id map directly (the threads of a row read the same two words), so the gather does not
+// wait for the lookup kernel, which records the accesses for the update beside it.
 template <int VEC>
 __global__ void __launch_bounds__(256) k_gather(const float* __restrict__ rows, const float* __restrict__ store, int32_t dim,
-                                                int64_t B, const int32_t* __restrict__ ids,
-                                                const int32_t* __restrict__ slots, float* __restrict__ out) {
+                                                int64_t B, int64_t num_ids, const int32_t* __restrict__ ids,
+                                                const int32_t* __restrict__ slot_of, float* __restrict__ out) {
     const int32_t per_row = dim / VEC;
     const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (t >= B * per_row) return;
     const int64_t b = t / per_row;
     const int32_t col = (int32_t)(t - b * per_row) * VEC;
-    const int32_t s = slots[b];
+    const int32_t id = ids[b];
+    const int32_t s = (id >= 0 && id < num_ids) ? slot_of[id] : -2;      // -1: not cached, -2: id out of range
     // the output and the rows of the backing store are touched once (non-temporal); the cached rows are
     // what should stay in the L2
     if (VEC == 4) {
         f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
         if (s >= 0) v = *reinterpret_cast<const f32x4*>(rows + (int64_t)s * dim + col);
-        else if (s == -1) v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(store + (int64_t)ids[b] * dim + col));
+        else if (s == -1) v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(store + (int64_t)id * dim + col));
         __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(out + b * dim + col));
     } else {
         float v = 0.f;
         if (s >= 0) v = rows[(int64_t)s * dim + col];
-        else if (s == -1) v = __builtin_nontemporal_load(store + (int64_t)ids[b] * dim + col);
+        else if (s == -1) v = __builtin_nontemporal_load(store + (int64_t)id * dim + col);
         __builtin_nontemporal_store(v, out + b * dim + col);
     }
 }
@@ -482,19 +485,27 @@ int tns_cache_fetch(tns_cache* cache, int64_t B, const int32_t* d_ids, const flo
     const int64_t C = cache->cfg.capacity, N = cache->cfg.num_ids;
     const int32_t maxrep = cache->max_replace;
 
-    hipLaunchKernelGGL(k_lookup, dim3(blocks_for(B)), dim3(256), 0, stream, st, policy, N, B, d_ids, w.slots, d_hit, w.ctl);
-    // From here the update (scores, distinct misses, victims: many short kernels over the score vector) runs on
-    // the cache's own stream beside the row gather, which is bound by memory bandwidth; both only read what the
-    // lookup wrote.  The insertion changes rows and maps and waits for both.
+    // Two chains that only meet at the insertion.  The caller's stream gathers the rows (bound by memory bandwidth;
+    // each row's threads look the slot up themselves).  The cache's own stream runs the lookup proper (hit flags,
+    // counters, recorded accesses, first occurrence of every missed id) and the update (scores, distinct misses,
+    // victims: many short kernels over the score vector).  Both only read the maps and rows; the insertion changes
+    // them and waits for both.
     const bool select = maxrep > 0 && policy != TNS_CACHE_FIFO;
-    const bool update = maxrep > 0 || policy == TNS_CACHE_LRU;
-    hipStream_t us = stream;
-    if (update) {
+    hipStream_t us = cache->side;
+    {
         hipError_t ef = hipEventRecord(cache->forked, stream);
-        if (ef == hipSuccess) ef = hipStreamWaitEvent(cache->side, cache->forked, 0);
+        if (ef == hipSuccess) ef = hipStreamWaitEvent(us, cache->forked, 0);
         if (ef != hipSuccess) return fail_hip(ef, "forking the cache update");
-        us = cache->side;
     }
+    const bool vec4 = dim % 4 == 0 && ((reinterpret_cast<uintptr_t>(store) | reinterpret_cast<uintptr_t>(d_out)) & 15) == 0;
+    if (vec4)
+        hipLaunchKernelGGL(k_gather<4>, dim3(blocks_for(B * (dim / 4))), dim3(256), 0, stream, st.rows, store, dim, B, N, d_ids,
+                           st.slot_of, d_out);
+    else
+        hipLaunchKernelGGL(k_gather<1>, dim3(blocks_for(B * dim)), dim3(256), 0, stream, st.rows, store, dim, B, N, d_ids,
+                           st.slot_of, d_out);
+
+    hipLaunchKernelGGL(k_lookup, dim3(blocks_for(B)), dim3(256), 0, us, st, policy, N, B, d_ids, w.slots, d_hit, w.ctl);
     // LRU: every score is decremented and the accessed entries are reset; done on the way by the first
     // pass of the victim selection when there is one
     if (policy == TNS_CACHE_LRU && !select)
@@ -517,22 +528,16 @@ int tns_cache_fetch(tns_cache* cache, int64_t B, const int32_t* d_ids, const flo
             compact_flagged(Victims{st.score, w.ctl, w.victims}, C, w.sums, us);
         }
     }
-    const bool vec4 = dim % 4 == 0 && ((reinterpret_cast<uintptr_t>(store) | reinterpret_cast<uintptr_t>(d_out)) & 15) == 0;
-    if (vec4)
-        hipLaunchKernelGGL(k_gather<4>, dim3(blocks_for(B * (dim / 4))), dim3(256), 0, stream, st.rows, store, dim, B, d_ids,
-                           w.slots, d_out);
-    else
-        hipLaunchKernelGGL(k_gather<1>, dim3(blocks_for(B * dim)), dim3(256), 0, stream, st.rows, store, dim, B, d_ids, w.slots,
-                           d_out);
-    if (update) {
-        hipError_t ej = hipEventRecord(cache->joined, cache->side);
+    // the first-occurrence marks of this batch are cleared for the next one (after the distinct misses were collected)
+    hipLaunchKernelGGL(k_clear_first, dim3(blocks_for(B)), dim3(256), 0, us, st.first_idx, B, d_ids, w.slots);
+    {
+        hipError_t ej = hipEventRecord(cache->joined, us);
         if (ej == hipSuccess) ej = hipStreamWaitEvent(stream, cache->joined, 0);
         if (ej != hipSuccess) return fail_hip(ej, "joining the cache update");
     }
     if (maxrep > 0)
         hipLaunchKernelGGL(k_insert, dim3(blocks_for(maxrep, 4)), dim3(256), 0, stream, st, policy, dim, store, w.new_ids, w.victims,
                            w.ctl);
-    hipLaunchKernelGGL(k_clear_first, dim3(blocks_for(B)), dim3(256), 0, stream, st.first_idx, B, d_ids, w.slots);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail_hip(e, "launching the cache kernels");
     return TNS_OK;

@@ -147,25 +147,37 @@ class Runner:
         self.out = None
 
 
-def streaming_rates(B, torch):
-    """The box's own ceilings: the library's read-only, write-only and copy kernels over 1 GiB (16-byte
-    accesses, non-temporal hint), GB/s of bytes moved.  Counter runs use the copy launch for calibration."""
+def streaming_rates(B, torch, read_per_write=None):
+    """The box's own ceilings from the library's streaming kernels over 1 GiB (16-byte accesses, non-temporal hint),
+    GB/s of bytes moved: read only, write only, a copy whose stores wait for all of a thread's loads (`copy`), the same
+    with every store issued as soon as its own load has arrived (`copy_interleaved`, the launch the counter runs
+    calibrate on), and a mix with the read:write byte ratio of the kernel under study (`mix`)."""
     dev = torch.device("cuda", 0)
     n = 1 << 30
     a = torch.empty(n, dtype=torch.uint8, device=dev)
     b = torch.empty(n, dtype=torch.uint8, device=dev)
     a.fill_(1)
     s = torch.cuda.current_stream().cuda_stream
-    rates = {}
-    for mode, name, traffic in ((1, "read", n), (2, "write", n), (0, "copy", 2 * n)):
-        B.tns_hbm_probe(mode, True, b.data_ptr(), a.data_ptr(), n, s)
+
+    def rate(fn, traffic):
+        fn()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(5):
-            B.tns_hbm_probe(mode, True, b.data_ptr(), a.data_ptr(), n, s)
+            fn()
         e1.record()
         torch.cuda.synchronize()
-        rates[name] = 5 * traffic / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        return 5 * traffic / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+    rates = {"read": rate(lambda: B.tns_hbm_probe(1, True, b.data_ptr(), a.data_ptr(), n, s), n),
+             "write": rate(lambda: B.tns_hbm_probe(2, True, b.data_ptr(), a.data_ptr(), n, s), n),
+             "copy": rate(lambda: B.tns_hbm_probe_mix(True, b.data_ptr(), n, a.data_ptr(), n, s), 2 * n),
+             "copy_interleaved": rate(lambda: B.tns_hbm_probe(0, True, b.data_ptr(), a.data_ptr(), n, s), 2 * n)}
+    if read_per_write:
+        rb = n if read_per_write >= 1 else int(n * read_per_write) // 16 * 16
+        wb = n if read_per_write <= 1 else int(n / read_per_write) // 16 * 16
+        rates["mix"] = rate(lambda: B.tns_hbm_probe_mix(True, b.data_ptr(), wb, a.data_ptr(), rb, s), rb + wb)
+        rates["mix_read_per_write"] = read_per_write
     del a, b
     return rates
 
@@ -360,8 +372,14 @@ def main() -> int:
         return r, fig
 
     r, head = measure_layout(args.layout, True)
-    rates = streaming_rates(B, torch)
     bm = head["byte_model"]
+    tr0 = head["traffic"]
+    if tr0 and not tr0["stale"]:
+        ratio = tr0["fetch_bytes"] / tr0["write_bytes"]        # what the kernel moved
+    else:
+        written = bm["parts"]["padded_write"] + bm["parts"]["dense_write"]
+        ratio = (bm["step"] - written) / written               # what the method needs
+    rates = streaming_rates(B, torch, ratio)
     ms_kernel = head["ms_per_launch"]
     achieved = bm["step"] / (ms_kernel * 1e-3) / 1e9
 
@@ -369,7 +387,8 @@ def main() -> int:
         if not tr or tr.get("bytes") is None:
             return None
         gbs = tr["bytes"] / (ms * 1e-3) / 1e9
-        return {"GBs": gbs, "frac_of_peak": gbs / HBM_PEAK_GBS, "frac_of_copy_kernel": gbs / rates["copy"], "waste_factor": tr["bytes"] / alg}
+        return {"GBs": gbs, "frac_of_peak": gbs / HBM_PEAK_GBS, "frac_of_copy_kernel": gbs / rates["copy"],
+                "frac_of_mix_kernel": gbs / rates["mix"] if "mix" in rates else None, "waste_factor": tr["bytes"] / alg}
 
     tr = head["traffic"]
     roofline = {"bound": "hbm", "kernel": head["kernel"], "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -351,6 +351,16 @@ TNS_API int64_t tns_node_blocks(const tns_plan *plan, int32_t instance, int32_t 
 TNS_API int tns_hbm_probe(int32_t mode, int32_t nontemporal, void *d_dst, const void *d_src, size_t bytes,
                           void *hip_stream);
 
+/*
+ * The same aid for a mix of the two directions: reads read_bytes from d_src and writes write_bytes to d_dst
+ * in one launch, the shorter stream spread evenly over the longer one, so that the memory system sees the
+ * read:write ratio of a kernel under study throughout (the sampling step reads about 1.6 bytes per byte it
+ * writes in the default layout, 0.9 in the prefix layout; a plain copy 1.0).  DEVICE buffers, 16-byte aligned,
+ * sizes positive multiples of 16 and at most 32 GiB each.
+ */
+TNS_API int tns_hbm_probe_mix(int32_t nontemporal, void *d_dst, size_t write_bytes, const void *d_src, size_t read_bytes,
+                              void *hip_stream);
+
 /* Release the plan (the dynamic graph object of section 5's interface), its host store and its device
    memory.  NULL is allowed. */
 TNS_API int tns_destroy(tns_plan *plan);

@@ -28,7 +28,7 @@ TNS_FLAG_WIDE_POSITIONS = 32
 TNS_FLAG_PREFIX_LAYOUT = 128
 TNS_TEST_FLAG_LOST_TILE = 64      # csrc/tns_test_hooks.h: for the library's own tests, not in the public header
 
-EXPORTS = ["tns_plan_create", "tns_set_sampler", "tns_add_edges", "tns_add_edges_device", "tns_delete_edges", "tns_delete_nodes", "tns_commit", "tns_workspace", "tns_run", "tns_run_status", "tns_run_static", "tns_workspace_khop", "tns_run_khop", "tns_compact", "tns_traffic_model", "tns_stats",
+EXPORTS = ["tns_plan_create", "tns_set_sampler", "tns_add_edges", "tns_add_edges_device", "tns_delete_edges", "tns_delete_nodes", "tns_commit", "tns_workspace", "tns_run", "tns_run_status", "tns_run_static", "tns_hbm_probe_mix", "tns_workspace_khop", "tns_run_khop", "tns_compact", "tns_traffic_model", "tns_stats",
            "tns_node_blocks", "tns_hbm_probe", "tns_destroy", "tns_strerror", "tns_last_error"]
 
 
@@ -113,6 +113,8 @@ def lib():
         L.tns_node_blocks.restype = C.c_int64
         L.tns_hbm_probe.argtypes = [C.c_int32, C.c_int32, vp, vp, C.c_size_t, vp]
         L.tns_hbm_probe.restype = C.c_int
+        L.tns_hbm_probe_mix.argtypes = [C.c_int32, vp, C.c_size_t, vp, C.c_size_t, vp]
+        L.tns_hbm_probe_mix.restype = C.c_int
         L.tns_destroy.argtypes = [vp]
         L.tns_destroy.restype = C.c_int
         L.tns_strerror.argtypes = [C.c_int]
@@ -283,6 +285,13 @@ def tns_hbm_probe(mode: int, nontemporal: bool, d_dst: int, d_src: int, nbytes: 
     """Streaming kernel of known traffic: mode 0 copy, 1 read, 2 write (raw device addresses)."""
     vp = lambda x: C.c_void_p(x or None)
     _check(lib().tns_hbm_probe(mode, 1 if nontemporal else 0, vp(d_dst), vp(d_src), nbytes, vp(hip_stream)), "tns_hbm_probe")
+
+
+def tns_hbm_probe_mix(nontemporal: bool, d_dst: int, write_bytes: int, d_src: int, read_bytes: int, hip_stream: int = 0) -> None:
+    """Streaming kernel that reads read_bytes and writes write_bytes, evenly interleaved (measurement aid)."""
+    vp = lambda x: C.c_void_p(x or None)
+    _check(lib().tns_hbm_probe_mix(1 if nontemporal else 0, vp(d_dst), write_bytes, vp(d_src), read_bytes, vp(hip_stream)),
+           "tns_hbm_probe_mix")
 
 
 def tns_destroy(plan) -> None:

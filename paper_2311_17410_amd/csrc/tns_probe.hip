@@ -50,7 +50,58 @@ __global__ void __launch_bounds__(kThreads) tns_probe_kernel(u32x4* __restrict__
     }
 }
 
+// Reads rv vectors of src and writes wv vectors of dst, the shorter stream spread evenly over the longer one:
+// workgroup g of G takes the g-th share of each stream (two divisions per workgroup, none per vector), loads its
+// share of src, then stores its share of dst.
+template <bool NT>
+__global__ void __launch_bounds__(kThreads) tns_probe_mix_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src, int64_t rv,
+                                                                 int64_t wv, unsigned sentinel) {
+    const int64_t g = blockIdx.x, G = gridDim.x;
+    const int64_t r_lo = g * rv / G, r_hi = (g + 1) * rv / G;        // g, G < 2^31 and rv, wv < 2^31: the products fit
+    const int64_t w_lo = g * wv / G, w_hi = (g + 1) * wv / G;
+    u32x4 v[kUnroll];
+#pragma unroll
+    for (int i = 0; i < kUnroll; ++i) {
+        const int64_t k = r_lo + (int64_t)i * kThreads + threadIdx.x;
+        v[i] = u32x4{sentinel, (unsigned)i, threadIdx.x, blockIdx.x};
+        if (k < r_hi) v[i] = ld<NT>(src + k);
+    }
+    unsigned acc = 0;
+#pragma unroll
+    for (int i = 0; i < kUnroll; ++i) acc ^= v[i].x;
+#pragma unroll
+    for (int i = 0; i < kUnroll; ++i) {
+        const int64_t k = w_lo + (int64_t)i * kThreads + threadIdx.x;
+        if (k < w_hi) {
+            v[i].w ^= acc;          // every store depends on every load of the thread
+            st<NT>(v[i], dst + k);
+        }
+    }
+}
+
 }  // namespace
+
+extern "C" int tns_hbm_probe_mix(int32_t nontemporal, void* d_dst, size_t write_bytes, const void* d_src, size_t read_bytes,
+                                 void* hip_stream) {
+    tns::clear_error();
+    if (!d_dst || !d_src) return tns::fail(TNS_EINVAL, "null buffer");
+    if (read_bytes % 16 || write_bytes % 16 || read_bytes < 16 || write_bytes < 16 ||
+        (reinterpret_cast<uintptr_t>(d_dst) | reinterpret_cast<uintptr_t>(d_src)) % 16)
+        return tns::fail(TNS_EINVAL, "sizes and addresses must be positive multiples of 16 bytes");
+    const int64_t rv = (int64_t)(read_bytes / 16), wv = (int64_t)(write_bytes / 16), n = rv > wv ? rv : wv;
+    const int64_t grid = (n + kThreads * kUnroll - 1) / (kThreads * kUnroll);      // a workgroup's share of either stream fits its registers
+    if (n >= (int64_t(1) << 31)) return tns::fail(TNS_ESIZE, "at most 32 GiB per stream: split the buffers");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (nontemporal)
+        hipLaunchKernelGGL((tns_probe_mix_kernel<true>), dim3((unsigned)grid), dim3(kThreads), 0, s, static_cast<u32x4*>(d_dst),
+                           static_cast<const u32x4*>(d_src), rv, wv, 0x9e3779b9u);
+    else
+        hipLaunchKernelGGL((tns_probe_mix_kernel<false>), dim3((unsigned)grid), dim3(kThreads), 0, s, static_cast<u32x4*>(d_dst),
+                           static_cast<const u32x4*>(d_src), rv, wv, 0x9e3779b9u);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return tns::fail_hip(e, "launching a probe kernel");
+    return TNS_OK;
+}
 
 extern "C" int tns_hbm_probe(int32_t mode, int32_t nontemporal, void* d_dst, const void* d_src, size_t bytes, void* hip_stream) {
     tns::clear_error();

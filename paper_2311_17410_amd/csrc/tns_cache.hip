@@ -59,34 +59,47 @@ __global__ void __launch_bounds__(256) k_rebuild_map(const int32_t* __restrict__
     }
 }
 
-// Lookup of the batch against the cache as it is before the update; accesses are recorded.
+// Lookup of the batch against the cache as it is before the update; accesses are recorded.  A thread takes
+// kLookupUnroll ids, one grid width apart, and runs each dependent step for all of them before the next.
+constexpr int kLookupUnroll = 4;
 __global__ void __launch_bounds__(256) k_lookup(CacheState c, int policy, int64_t num_ids, int64_t B,
                                                 const int32_t* __restrict__ ids, int32_t* __restrict__ slots,
                                                 uint8_t* __restrict__ hit, Ctl* ctl) {
-    const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (blockIdx.x == 0) {          // scalars of this update
         if (threadIdx.x == 0) { ctl->prefix = 0; ctl->mask = 0; ctl->remaining = 0; ctl->m = 0; ctl->n_unique = 0; }
         ctl->hist[threadIdx.x] = 0;
     }
-    int is_hit = 0, is_miss = 0;
-    if (b < B) {
-        const int32_t id = ids[b];
-        int32_t s = -2;                                   // -2: id out of range
-        if (id >= 0 && id < num_ids) {
-            s = c.slot_of[id];
-            if (s >= 0) {
-                is_hit = 1;
-                if (policy == TNS_CACHE_LRU) c.touched[s] = 1;
-                else if (policy == TNS_CACHE_LFU) atomicAdd(&c.score[s], 1);
-            } else {
-                is_miss = 1;
-                atomicMin(&c.first_idx[id], (int32_t)b);  // first occurrence of a missed id
-            }
-        }
-        slots[b] = s;
-        if (hit) hit[b] = (uint8_t)is_hit;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    const int64_t b0 = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    int32_t id[kLookupUnroll], s[kLookupUnroll];
+#pragma unroll
+    for (int u = 0; u < kLookupUnroll; ++u) id[u] = ids[min(b0 + (int64_t)u * stride, B - 1)];
+#pragma unroll
+    for (int u = 0; u < kLookupUnroll; ++u) {
+        const bool in_range = id[u] >= 0 && id[u] < num_ids;
+        s[u] = c.slot_of[in_range ? id[u] : 0];
+        if (!in_range) s[u] = -2;                         // -2: id out of range
     }
-    const unsigned long long h = __popcll(__ballot(is_hit)), m = __popcll(__ballot(is_miss));
+    unsigned long long h = 0, m = 0;
+#pragma unroll
+    for (int u = 0; u < kLookupUnroll; ++u) {
+        const int64_t b = b0 + (int64_t)u * stride;
+        int is_hit = 0, is_miss = 0;
+        if (b < B) {
+            if (s[u] >= 0) {
+                is_hit = 1;
+                if (policy == TNS_CACHE_LRU) c.touched[s[u]] = 1;
+                else if (policy == TNS_CACHE_LFU) atomicAdd(&c.score[s[u]], 1);
+            } else if (s[u] == -1) {
+                is_miss = 1;
+                atomicMin(&c.first_idx[id[u]], (int32_t)b);   // first occurrence of a missed id
+            }
+            slots[b] = s[u];
+            if (hit) hit[b] = (uint8_t)is_hit;
+        }
+        h += __popcll(__ballot(is_hit));
+        m += __popcll(__ballot(is_miss));
+    }
     if ((threadIdx.x & (kWave - 1)) == 0) {
         unsigned long long* mine = c.counters + (size_t)((blockIdx.x * 4 + (threadIdx.x >> 6)) % kStripes) * 3;
         if (h) atomicAdd(&mine[0], h);
@@ -98,30 +111,57 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // out[b] = cached row or row of the backing store; VEC floats per thread, rows stay coalesced
 // The slot comes from the id map directly (the threads of a row read the same two words), so the gather does not
-// wait for the lookup kernel, which records the accesses for the update beside it.
+// wait for the lookup kernel, which records the accesses for the update beside it.  A thread moves kGatherUnroll
+// pieces, one grid width apart, and runs each dependent step (id, slot, row, store) for all of them before the next:
+// the kernel is a copy, and a copy on this machine is bound by how much each compute unit has in flight.
+constexpr int kGatherUnroll = 8;
 template <int VEC>
 __global__ void __launch_bounds__(256) k_gather(const float* __restrict__ rows, const float* __restrict__ store, int32_t dim,
                                                 int64_t B, int64_t num_ids, const int32_t* __restrict__ ids,
                                                 const int32_t* __restrict__ slot_of, float* __restrict__ out) {
     const int32_t per_row = dim / VEC;
-    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (t >= B * per_row) return;
-    const int64_t b = t / per_row;
-    const int32_t col = (int32_t)(t - b * per_row) * VEC;
-    const int32_t id = ids[b];
-    const int32_t s = (id >= 0 && id < num_ids) ? slot_of[id] : -2;      // -1: not cached, -2: id out of range
+    const int64_t total = B * per_row;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    const int64_t t0 = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    int64_t b[kGatherUnroll];
+    int32_t col[kGatherUnroll], id[kGatherUnroll], s[kGatherUnroll];
+#pragma unroll
+    for (int u = 0; u < kGatherUnroll; ++u) {
+        const int64_t t = min(t0 + (int64_t)u * stride, total - 1);      // clamped: no load sits in a branch
+        b[u] = t / per_row;
+        col[u] = (int32_t)(t - b[u] * per_row) * VEC;
+        id[u] = ids[b[u]];
+    }
+#pragma unroll
+    for (int u = 0; u < kGatherUnroll; ++u) {
+        const bool in_range = id[u] >= 0 && id[u] < num_ids;
+        s[u] = slot_of[in_range ? id[u] : 0];
+        if (!in_range) s[u] = -2;                                         // -1: not cached, -2: id out of range
+    }
     // the output and the rows of the backing store are touched once (non-temporal); the cached rows are
     // what should stay in the L2
     if (VEC == 4) {
-        f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
-        if (s >= 0) v = *reinterpret_cast<const f32x4*>(rows + (int64_t)s * dim + col);
-        else if (s == -1) v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(store + (int64_t)id * dim + col));
-        __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(out + b * dim + col));
+        f32x4 v[kGatherUnroll];
+#pragma unroll
+        for (int u = 0; u < kGatherUnroll; ++u) {
+            const float* src = s[u] >= 0 ? rows + (int64_t)s[u] * dim + col[u] : store + (int64_t)(s[u] == -1 ? id[u] : 0) * dim + col[u];
+            v[u] = s[u] >= 0 ? *reinterpret_cast<const f32x4*>(src) : __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(src));
+            if (s[u] == -2) v[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int u = 0; u < kGatherUnroll; ++u)
+            if (t0 + (int64_t)u * stride < total) __builtin_nontemporal_store(v[u], reinterpret_cast<f32x4*>(out + b[u] * dim + col[u]));
     } else {
-        float v = 0.f;
-        if (s >= 0) v = rows[(int64_t)s * dim + col];
-        else if (s == -1) v = __builtin_nontemporal_load(store + (int64_t)id * dim + col);
-        __builtin_nontemporal_store(v, out + b * dim + col);
+        float v[kGatherUnroll];
+#pragma unroll
+        for (int u = 0; u < kGatherUnroll; ++u) {
+            const float* src = s[u] >= 0 ? rows + (int64_t)s[u] * dim + col[u] : store + (int64_t)(s[u] == -1 ? id[u] : 0) * dim + col[u];
+            v[u] = s[u] >= 0 ? *src : __builtin_nontemporal_load(src);
+            if (s[u] == -2) v[u] = 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < kGatherUnroll; ++u)
+            if (t0 + (int64_t)u * stride < total) __builtin_nontemporal_store(v[u], out + b[u] * dim + col[u]);
     }
 }
 
@@ -203,11 +243,31 @@ __global__ void __launch_bounds__(1024) k_flag_scan_sums(const F f, int64_t* __r
     if (threadIdx.x == 0) f.total(s_carry);
 }
 
-template <class F>
+// FOLD: `sums` holds the raw tile sums and every workgroup adds up those of the tiles before it by itself (at most
+// kFoldTiles of them, read from the L2); the last one also hands the total to the functor.  This saves the
+// one-workgroup scan kernel between the two, which is slow beside a kernel that saturates the memory system.
+constexpr int64_t kFoldTiles = 2048;
+template <class F, bool FOLD>
 __global__ void __launch_bounds__(256) k_flag_collect(const F f, int64_t n, const int64_t* __restrict__ sums) {
-    __shared__ int64_t s_w[4];
+    __shared__ int64_t s_w[4], s_t[4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kPerThread;
+    int64_t tile_off = 0;
+    if (FOLD) {
+        int64_t part = 0;
+        for (int64_t t0 = 0; t0 < (int64_t)blockIdx.x; t0 += 256 * 4) {
+            int64_t v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t t = t0 + u * 256 + threadIdx.x;
+                v[u] = sums[min(t, (int64_t)blockIdx.x)];          // clamped: no load sits in a branch
+                if (t >= (int64_t)blockIdx.x) v[u] = 0;
+            }
+            part += v[0] + v[1] + v[2] + v[3];
+        }
+        part = wave_inclusive_scan64(part, lane);
+        if (lane == 63) s_t[wave] = part;
+    }
     int64_t c[kPerThread], sum = 0;
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i) {
@@ -217,8 +277,11 @@ __global__ void __launch_bounds__(256) k_flag_collect(const F f, int64_t n, cons
     const int64_t inc = wave_inclusive_scan64(sum, lane);
     if (lane == 63) s_w[wave] = inc;
     __syncthreads();
-    int64_t before = sums[blockIdx.x] + inc - sum;
+    if (FOLD) tile_off = s_t[0] + s_t[1] + s_t[2] + s_t[3];
+    else tile_off = sums[blockIdx.x];
+    int64_t before = tile_off + inc - sum;
     for (int w = 0; w < wave; ++w) before += s_w[w];
+    if (FOLD && blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) f.total(tile_off + s_w[0] + s_w[1] + s_w[2] + s_w[3]);
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i) {
         if (c[i]) f.emit(base + i, before);
@@ -363,9 +426,14 @@ inline size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 template <class F>
 void compact_flagged(const F& f, int64_t n, int64_t* sums, hipStream_t stream) {
     const int64_t tiles = (n + kScanTile - 1) / kScanTile;
+    if (tiles > 0 && tiles <= kFoldTiles) {
+        hipLaunchKernelGGL((k_flag_tile_sums<F>), dim3((unsigned)tiles), dim3(256), 0, stream, f, n, sums);
+        hipLaunchKernelGGL((k_flag_collect<F, true>), dim3((unsigned)tiles), dim3(256), 0, stream, f, n, sums);
+        return;
+    }
     if (tiles > 0) hipLaunchKernelGGL((k_flag_tile_sums<F>), dim3((unsigned)tiles), dim3(256), 0, stream, f, n, sums);
     hipLaunchKernelGGL((k_flag_scan_sums<F>), dim3(1), dim3(1024), 0, stream, f, sums, tiles);
-    if (tiles > 0) hipLaunchKernelGGL((k_flag_collect<F>), dim3((unsigned)tiles), dim3(256), 0, stream, f, n, sums);
+    if (tiles > 0) hipLaunchKernelGGL((k_flag_collect<F, false>), dim3((unsigned)tiles), dim3(256), 0, stream, f, n, sums);
 }
 
 }  // namespace
@@ -499,13 +567,13 @@ int tns_cache_fetch(tns_cache* cache, int64_t B, const int32_t* d_ids, const flo
     }
     const bool vec4 = dim % 4 == 0 && ((reinterpret_cast<uintptr_t>(store) | reinterpret_cast<uintptr_t>(d_out)) & 15) == 0;
     if (vec4)
-        hipLaunchKernelGGL(k_gather<4>, dim3(blocks_for(B * (dim / 4))), dim3(256), 0, stream, st.rows, store, dim, B, N, d_ids,
+        hipLaunchKernelGGL(k_gather<4>, dim3(blocks_for((B * (dim / 4) + kGatherUnroll - 1) / kGatherUnroll)), dim3(256), 0, stream, st.rows, store, dim, B, N, d_ids,
                            st.slot_of, d_out);
     else
-        hipLaunchKernelGGL(k_gather<1>, dim3(blocks_for(B * dim)), dim3(256), 0, stream, st.rows, store, dim, B, N, d_ids,
+        hipLaunchKernelGGL(k_gather<1>, dim3(blocks_for((B * dim + kGatherUnroll - 1) / kGatherUnroll)), dim3(256), 0, stream, st.rows, store, dim, B, N, d_ids,
                            st.slot_of, d_out);
 
-    hipLaunchKernelGGL(k_lookup, dim3(blocks_for(B)), dim3(256), 0, us, st, policy, N, B, d_ids, w.slots, d_hit, w.ctl);
+    hipLaunchKernelGGL(k_lookup, dim3(blocks_for((B + kLookupUnroll - 1) / kLookupUnroll)), dim3(256), 0, us, st, policy, N, B, d_ids, w.slots, d_hit, w.ctl);
     // LRU: every score is decremented and the accessed entries are reset; done on the way by the first
     // pass of the victim selection when there is one
     if (policy == TNS_CACHE_LRU && !select)

@@ -1,6 +1,9 @@
 // C ABI of the library (include/tns.h): plan lifetime, ingestion, commit, run, statistics.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+#include <atomic>
+#include <chrono>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -66,7 +69,10 @@ struct DeviceStore {
     DeviceArray<tns::NodeAux> aux;
     DeviceArray<unsigned char> ws;              // scratch of the ingestion kernels, grown on demand
     tns::IngestStatus* d_status = nullptr;
-    tns::IngestStatus* h_status = nullptr;      // page-locked landing place of the status read-backs
+    tns::IngestStatus* h_status = nullptr;      // page-locked landing place of the status read-backs, followed by a
+                                                // sequence word; the device can write both (mapped, coherent)
+    tns::IngestStatus* h_status_dev = nullptr;  // the same memory as the device addresses it
+    unsigned long long seq = 0;                 // batches planned by the short pipeline
     std::vector<tns::InstanceTotals> totals;   // per instance: edges, blocks, slots, running edge id, deleted
 };
 
@@ -166,7 +172,13 @@ int ensure_device_store(tns_plan* plan, hipStream_t stream) {
     if (e == hipSuccess) e = hipMemsetAsync(ds.aux.ptr, 0, (size_t)total_nodes * sizeof(tns::NodeAux), stream);
     tns::IngestStatus* st = nullptr;
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&st), sizeof(tns::IngestStatus));
-    if (e == hipSuccess && !ds.h_status) e = hipHostMalloc(reinterpret_cast<void**>(&ds.h_status), sizeof(tns::IngestStatus), hipHostMallocDefault);
+    if (e == hipSuccess && !ds.h_status) {
+        e = hipHostMalloc(reinterpret_cast<void**>(&ds.h_status), 2 * sizeof(tns::IngestStatus), hipHostMallocMapped | hipHostMallocCoherent);
+        if (e == hipSuccess) {
+            std::memset(ds.h_status, 0, 2 * sizeof(tns::IngestStatus));
+            e = hipHostGetDevicePointer(reinterpret_cast<void**>(&ds.h_status_dev), ds.h_status, 0);
+        }
+    }
     if (e == hipSuccess) e = hipMemsetAsync(st, 0, sizeof(tns::IngestStatus), stream);
     if (e == hipSuccess) e = tns::ingest_status_reset(st, stream);
     if (e == hipSuccess) e = hipStreamSynchronize(stream);
@@ -371,10 +383,32 @@ int tns_add_edges_device(tns_plan* plan, int32_t instance, const int32_t* d_src,
     // Batches of stream size take the short planning pipeline, which assumes time order; if the status says the
     // batch was not in time order (nothing has been changed yet) the general pipeline plans it again.
     bool fast = tns::ingest_fast_ok(m, plan->cfg.num_nodes);
+    if (fast && ds.h_status_dev) {
+        a.host_status = ds.h_status_dev;
+        a.host_seq = reinterpret_cast<unsigned long long*>(ds.h_status_dev + 1);
+        a.seq = ++ds.seq;
+    }
     hipError_t e = fast ? tns::ingest_plan_fast(a, stream) : tns::ingest_plan(a, stream);
     if (e != hipSuccess) return fail_hip(e, "launching the ingestion planning kernels");
     tns::IngestStatus st;
-    if ((rc = read_status(plan, stream, st, "waiting for the ingestion plan"))) return rc;
+    bool polled = false;
+    if (a.host_status) {
+        // The plan's last workgroup writes the record into host memory and then the batch's sequence number: picked
+        // up here by polling, which is some 20 us sooner than a copy and a wait for the stream.  The wait is bounded;
+        // past the bound (or with an internal error in the record) the ordinary read-back takes over.
+        const volatile unsigned long long* seq_word = reinterpret_cast<const volatile unsigned long long*>(ds.h_status + 1);
+        const auto t0 = std::chrono::steady_clock::now();
+        int spins = 0;
+        while (*seq_word != a.seq) {
+            if ((++spins & 1023) == 0 && std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(2)) break;
+        }
+        if (*seq_word == a.seq) {
+            std::atomic_thread_fence(std::memory_order_acquire);
+            st = *ds.h_status;
+            polled = st.internal == 0;
+        }
+    }
+    if (!polled && (rc = read_status(plan, stream, st, "waiting for the ingestion plan"))) return rc;
     if (fast && st.unsorted && st.err_word == ~0ull) {
         fast = false;
         if ((e = tns::ingest_plan(a, stream)) != hipSuccess) return fail_hip(e, "launching the ingestion planning kernels");

@@ -59,6 +59,12 @@ struct IngestArgs {
     // scratch
     void* workspace;      // ingest_workspace_bytes(m)
     IngestStatus* status;
+    // optional (short pipeline only): a copy of *status in page-locked host memory that the device can write, and a
+    // sequence word next to it; the plan's last workgroup copies the record there and then stores `seq`, so that
+    // the host can pick the plan up by polling instead of waiting for the stream
+    IngestStatus* host_status;
+    unsigned long long* host_seq;
+    unsigned long long seq;
 };
 
 constexpr int64_t kMaxDeviceBatch = kMaxBlockEdges;   // one new block always takes the rest of a node's share

@@ -632,7 +632,7 @@ __global__ void __launch_bounds__(kThreads) k_fast_keys(const IngestArgs a, uint
         }
         if (threadIdx.x == 0) {
             seg_scan->ticket = 0; seg_scan->error = 0;
-            lines_scan->ticket = 0; lines_scan->error = 0;
+            lines_scan->ticket = 0; lines_scan->error = 0; lines_scan->pad[0] = 0;      // pad[0]: plan workgroups that are done
             dir_scan->ticket = 0; dir_scan->error = 0;
         }
     }
@@ -853,6 +853,25 @@ __global__ void __launch_bounds__(kPlanThreads) k_fast_plan(const IngestArgs a, 
         a.status->total_dir = s_excl_dir + tot_dir;
     }
     add_block_totals<kWaves>(a.status, blocks, slots);
+    if (a.host_status) {
+        // The workgroup that finishes last hands the record to the host.  Every workgroup's updates of the record
+        // have been performed when it counts itself in (the barrier waits for the threads' memory operations, the
+        // fence orders thread 0's own); the copy reads past the caches of this compute unit.
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            __threadfence();
+            const uint32_t before = atomicAdd(&lines_scan->pad[0], 1u);
+            if (before == (uint32_t)plan_tiles - 1u) {
+                __threadfence();
+                const unsigned long long* src = reinterpret_cast<const unsigned long long*>(a.status);
+                unsigned long long* dst = reinterpret_cast<unsigned long long*>(a.host_status);
+                for (int i = 0; i < (int)(sizeof(IngestStatus) / 8); ++i)
+                    dst[i] = __hip_atomic_load(&src[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __threadfence_system();
+                __hip_atomic_store(a.host_seq, a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+            }
+        }
+    }
 }
 
 // ---- deletion, statistics ------------------------------------------------------------------

@@ -263,7 +263,7 @@ def side_config(B, torch, W, name: str, layout: str, steps: int):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C5", help="C1..C5 (C5 = the headline: n = 2^28)")
     ap.add_argument("--log2n", type=int, default=None, help="override the stream length of C3/C5 (experiments)")

@@ -26,11 +26,15 @@ constexpr int kStripes = 64;
 
 // Device-side scalars of one fetch.
 struct Ctl {
-    uint32_t prefix, mask;                // radix select: decided high bits of the threshold key
-    int32_t remaining;                    // how many entries are still to be taken among keys matching the prefix
+    uint32_t prefix, mask;                // radix select: decided high bits of the threshold key (final, after four passes)
+    int32_t remaining;                    // how many entries are still to be taken among keys equal to the threshold
     int32_t m;                            // entries replaced by this update
     int32_t n_unique;                     // distinct missed ids of the batch
-    int32_t hist[256];
+    // state after each pass of the radix select (index p = after p passes; 0 = nothing decided) and the histogram
+    // each pass fills: a pass's digit is picked by the kernel that follows it, in every workgroup's prologue
+    uint32_t sel_prefix[5], sel_mask[5];
+    int32_t sel_rem[5];
+    int32_t hist[4][256];
 };
 
 struct CacheState {
@@ -67,7 +71,8 @@ __global__ void __launch_bounds__(256) k_lookup(CacheState c, int policy, int64_
                                                 uint8_t* __restrict__ hit, Ctl* ctl) {
     if (blockIdx.x == 0) {          // scalars of this update
         if (threadIdx.x == 0) { ctl->prefix = 0; ctl->mask = 0; ctl->remaining = 0; ctl->m = 0; ctl->n_unique = 0; }
-        ctl->hist[threadIdx.x] = 0;
+#pragma unroll
+        for (int p4 = 0; p4 < 4; ++p4) ctl->hist[p4][threadIdx.x] = 0;
     }
     const int64_t stride = (int64_t)gridDim.x * 256;
     const int64_t b0 = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -248,20 +253,20 @@ __global__ void __launch_bounds__(1024) k_flag_scan_sums(const F f, int64_t* __r
 // one-workgroup scan kernel between the two, which is slow beside a kernel that saturates the memory system.
 constexpr int64_t kFoldTiles = 2048;
 template <class F, bool FOLD>
-__global__ void __launch_bounds__(256) k_flag_collect(const F f, int64_t n, const int64_t* __restrict__ sums) {
+__device__ __forceinline__ void flag_collect_body(const F& f, int64_t n, const int64_t* __restrict__ sums, int64_t bid, int64_t nblocks) {
     __shared__ int64_t s_w[4], s_t[4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kPerThread;
+    const int64_t base = bid * kScanTile + (int64_t)threadIdx.x * kPerThread;
     int64_t tile_off = 0;
     if (FOLD) {
         int64_t part = 0;
-        for (int64_t t0 = 0; t0 < (int64_t)blockIdx.x; t0 += 256 * 4) {
+        for (int64_t t0 = 0; t0 < bid; t0 += 256 * 4) {
             int64_t v[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int64_t t = t0 + u * 256 + threadIdx.x;
-                v[u] = sums[min(t, (int64_t)blockIdx.x)];          // clamped: no load sits in a branch
-                if (t >= (int64_t)blockIdx.x) v[u] = 0;
+                v[u] = sums[min(t, bid)];          // clamped: no load sits in a branch
+                if (t >= bid) v[u] = 0;
             }
             part += v[0] + v[1] + v[2] + v[3];
         }
@@ -278,15 +283,20 @@ __global__ void __launch_bounds__(256) k_flag_collect(const F f, int64_t n, cons
     if (lane == 63) s_w[wave] = inc;
     __syncthreads();
     if (FOLD) tile_off = s_t[0] + s_t[1] + s_t[2] + s_t[3];
-    else tile_off = sums[blockIdx.x];
+    else tile_off = sums[bid];
     int64_t before = tile_off + inc - sum;
     for (int w = 0; w < wave; ++w) before += s_w[w];
-    if (FOLD && blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) f.total(tile_off + s_w[0] + s_w[1] + s_w[2] + s_w[3]);
+    if (FOLD && bid == nblocks - 1 && threadIdx.x == 0) f.total(tile_off + s_w[0] + s_w[1] + s_w[2] + s_w[3]);
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i) {
         if (c[i]) f.emit(base + i, before);
         before += c[i];
     }
+}
+
+template <class F, bool FOLD>
+__global__ void __launch_bounds__(256) k_flag_collect(const F f, int64_t n, const int64_t* __restrict__ sums) {
+    flag_collect_body<F, FOLD>(f, n, sums, blockIdx.x, gridDim.x);
 }
 
 // Distinct missed ids in the order of their first occurrence (the flag: a missed row that is the first
@@ -310,29 +320,66 @@ struct NewIds {
     }
 };
 
-__global__ void __launch_bounds__(256) k_clear_first(int32_t* __restrict__ first_idx, int64_t B, const int32_t* __restrict__ ids,
-                                                     const int32_t* __restrict__ slots) {
-    const int64_t b = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (b < B && slots[b] == -1) first_idx[ids[b]] = kNoIndex;
-}
 
 // ---- victims: the m entries with the lowest (score, slot) --------------------------------------
 
 __device__ __forceinline__ uint32_t score_key(int32_t score) { return (uint32_t)score ^ 0x80000000u; }   // unsigned order = signed order
 
-// One pass of the radix select (8 bits, most significant first), two launches.  First the histogram of
-// the digit over the entries whose decided high bits match.  LRU_UPDATE (first pass under LRU): the scores
-// are brought up to date on the way (every score decremented, entries accessed by the batch reset to 0).
+// Radix select of the m-th smallest key, 8 bits per pass, most significant first.  A pass is one launch that
+// histograms the digit over the entries whose decided high bits match; the digit in which the remaining-th
+// smallest key falls is picked by the NEXT kernel, by every workgroup for itself in its prologue (a scan over
+// 256 bins), so a pass needs no launch of its own for the pick.  Workgroup 0 also stores the state for whoever
+// reads it later.  Called by all 256 threads of a workgroup; returns the state after `pass` passes.
+struct SelState { uint32_t prefix, mask; int32_t rem; };
+__device__ __forceinline__ SelState select_pick(Ctl* ctl, int pass /* 1..4 */, bool store) {
+    __shared__ int32_t s_w[4];
+    __shared__ SelState s_out;
+    SelState prev;
+    if (pass == 1) { prev.prefix = 0; prev.mask = 0; prev.rem = ctl->m; }
+    else { prev.prefix = ctl->sel_prefix[pass - 1]; prev.mask = ctl->sel_mask[pass - 1]; prev.rem = ctl->sel_rem[pass - 1]; }
+    const int shift = 32 - 8 * pass;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int32_t h = ctl->hist[pass - 1][threadIdx.x];
+    int32_t inc = wave_inclusive_scan(h, lane);
+    if (lane == 63) s_w[wave] = inc;
+    __syncthreads();
+    for (int w = 0; w < wave; ++w) inc += s_w[w];
+    // the first bin whose inclusive count reaches rem; bin 255 if none does
+    const bool mine = (inc >= prev.rem && inc - h < prev.rem) || (threadIdx.x == 255 && inc < prev.rem);
+    if (mine) {
+        s_out.prefix = prev.prefix | ((uint32_t)threadIdx.x << shift);
+        s_out.mask = prev.mask | (255u << shift);
+        s_out.rem = prev.rem - (inc - h);             // entries to take among keys equal to the threshold so far
+    }
+    __syncthreads();
+    const SelState out = s_out;
+    if (store && threadIdx.x == 0) {
+        ctl->sel_prefix[pass] = out.prefix; ctl->sel_mask[pass] = out.mask; ctl->sel_rem[pass] = out.rem;
+        if (pass == 4) { ctl->prefix = out.prefix; ctl->mask = out.mask; ctl->remaining = out.rem; }
+    }
+    __syncthreads();
+    return out;
+}
+
+// Histogram of pass `pass` (0..3).  LRU_UPDATE (pass 0 under LRU): the scores are brought up to date on the way
+// (every score decremented, entries accessed by the batch reset to 0); that pass does not know yet whether
+// anything will be replaced and histograms regardless.  `bid` / `nb`: this workgroup's index and the number of
+// workgroups that share the pass (the kernel may hold other work in its other workgroups).
 template <bool LRU_UPDATE>
-__global__ void __launch_bounds__(256) k_select_hist(int32_t* __restrict__ score, int32_t* __restrict__ touched, int64_t capacity,
-                                                     int shift, Ctl* ctl) {
+__device__ __forceinline__ void select_hist_body(int32_t* __restrict__ score, int32_t* __restrict__ touched, int64_t capacity,
+                                                 int pass, Ctl* ctl, int64_t bid, int64_t nb) {
     __shared__ int32_t s_h[256];
-    const bool active = ctl->m > 0;
-    if (!LRU_UPDATE && !active) return;
+    uint32_t prefix = 0, mask = 0;
+    if (pass > 0) {
+        if (ctl->m <= 0) return;
+        const SelState st = select_pick(ctl, pass, bid == 0);
+        prefix = st.prefix;
+        mask = st.mask;
+    }
+    const int shift = 24 - 8 * pass;
     s_h[threadIdx.x] = 0;
     __syncthreads();
-    const uint32_t prefix = ctl->prefix, mask = ctl->mask;
-    for (int64_t s = (int64_t)blockIdx.x * 256 + threadIdx.x; s < capacity; s += (int64_t)gridDim.x * 256) {
+    for (int64_t s = bid * 256 + threadIdx.x; s < capacity; s += nb * 256) {
         int32_t sc = score[s];
         if (LRU_UPDATE) {
             sc = touched[s] ? 0 : sc - 1;
@@ -340,34 +387,16 @@ __global__ void __launch_bounds__(256) k_select_hist(int32_t* __restrict__ score
             touched[s] = 0;
         }
         const uint32_t k = score_key(sc);
-        if (active && (k & mask) == prefix) atomicAdd(&s_h[(k >> shift) & 255u], 1);
+        if ((k & mask) == prefix) atomicAdd(&s_h[(k >> shift) & 255u], 1);
     }
-    if (!active) return;
     __syncthreads();
-    if (s_h[threadIdx.x]) atomicAdd(&ctl->hist[threadIdx.x], s_h[threadIdx.x]);
+    if (s_h[threadIdx.x]) atomicAdd(&ctl->hist[pass][threadIdx.x], s_h[threadIdx.x]);
 }
 
-// Then one workgroup picks the digit in which the remaining-th smallest key falls, and clears the histogram.
-__global__ void __launch_bounds__(256) k_select_digit(int shift, Ctl* ctl) {
-    __shared__ int32_t s_w[4];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int32_t h = ctl->hist[threadIdx.x];
-    ctl->hist[threadIdx.x] = 0;
-    if (ctl->m <= 0) return;
-    int32_t inc = wave_inclusive_scan(h, lane);
-    if (lane == 63) s_w[wave] = inc;
-    __syncthreads();
-    for (int w = 0; w < wave; ++w) inc += s_w[w];
-    const int32_t rem = ctl->remaining;
-    const uint32_t prefix = ctl->prefix, mask = ctl->mask;
-    // the first bin whose inclusive count reaches rem; bin 255 if none does
-    const bool mine = (inc >= rem && inc - h < rem) || (threadIdx.x == 255 && inc < rem);
-    __syncthreads();
-    if (mine) {
-        ctl->prefix = prefix | ((uint32_t)threadIdx.x << shift);
-        ctl->mask = mask | (255u << shift);
-        ctl->remaining = rem - (inc - h);           // entries to take among keys equal to the threshold so far
-    }
+template <bool LRU_UPDATE>
+__global__ void __launch_bounds__(256) k_select_hist(int32_t* __restrict__ score, int32_t* __restrict__ touched, int64_t capacity,
+                                                     int pass, Ctl* ctl) {
+    select_hist_body<LRU_UPDATE>(score, touched, capacity, pass, ctl, blockIdx.x, gridDim.x);
 }
 
 // The victims in ascending slot order: every entry below the threshold key and the first `remaining`
@@ -376,11 +405,11 @@ struct Victims {
     const int32_t* score;
     const Ctl* ctl;
     int32_t* victims;
-    __device__ int64_t count(int64_t s) const {
-        if (ctl->m <= 0) return 0;
-        const uint32_t k = score_key(score[s]), t = ctl->prefix;
+    __device__ int64_t count_with(int64_t s, uint32_t t) const {
+        const uint32_t k = score_key(score[s]);
         return k < t ? (int64_t(1) << 32) : (k == t ? 1 : 0);
     }
+    __device__ int64_t count(int64_t s) const { return ctl->m <= 0 ? 0 : count_with(s, ctl->prefix); }
     __device__ void emit(int64_t s, int64_t before) const {
         const int64_t below_before = before >> 32, eq_before = before & 0xffffffffll, rem = ctl->remaining;
         const bool below = score_key(score[s]) < ctl->prefix;
@@ -388,6 +417,37 @@ struct Victims {
     }
     __device__ void total(int64_t) const {}
 };
+
+// Tile sums of the victims' compaction; the prologue picks the last digit of the radix select (the threshold is
+// final from here on: workgroup 0 stores it for the collect kernel).
+__global__ void __launch_bounds__(256) k_victims_tile_sums(const Victims f, Ctl* ctl, int64_t n, int64_t* __restrict__ sums) {
+    __shared__ int64_t s_w[4];
+    int64_t v = 0;
+    if (ctl->m > 0) {
+        const SelState st = select_pick(ctl, 4, blockIdx.x == 0);
+        const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kPerThread;
+#pragma unroll
+        for (int i = 0; i < kPerThread; ++i)
+            if (base + i < n) v += f.count_with(base + i, st.prefix);
+    }
+    const int lane = threadIdx.x & 63;
+    v = wave_inclusive_scan64(v, lane);
+    if (lane == 63) s_w[threadIdx.x >> 6] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) sums[blockIdx.x] = s_w[0] + s_w[1] + s_w[2] + s_w[3];
+}
+
+
+// Two independent pieces of the update in one launch (the chain of short launches is what the update costs):
+// workgroups [0, tiles) collect the distinct missed ids (which also fixes m), the other `hb` workgroups run pass 0
+// of the radix select over the scores, which depends on the lookup only.
+template <bool LRU_UPDATE>
+__global__ void __launch_bounds__(256) k_newids_collect_hist0(const NewIds f, int64_t n, const int64_t* __restrict__ sums, int64_t tiles,
+                                                              int32_t* __restrict__ score, int32_t* __restrict__ touched,
+                                                              int64_t capacity, Ctl* ctl, int64_t hb) {
+    if ((int64_t)blockIdx.x < tiles) flag_collect_body<NewIds, true>(f, n, sums, blockIdx.x, tiles);
+    else select_hist_body<LRU_UPDATE>(score, touched, capacity, 0, ctl, (int64_t)blockIdx.x - tiles, hb);
+}
 
 __global__ void __launch_bounds__(256) k_fifo_victims(int64_t capacity, int32_t max_replace, int64_t* ring, const Ctl* ctl,
                                                       int32_t* __restrict__ victims) {
@@ -399,11 +459,11 @@ __global__ void __launch_bounds__(256) k_fifo_victims(int64_t capacity, int32_t 
 __global__ void k_fifo_advance(int64_t capacity, int64_t* ring, const Ctl* ctl) { *ring = (*ring + ctl->m) % capacity; }
 
 // one wave per replaced entry: maps, score, row copy from the backing store
-__global__ void __launch_bounds__(256) k_insert(CacheState c, int policy, int32_t dim, const float* __restrict__ store,
-                                                const int32_t* __restrict__ new_ids, const int32_t* __restrict__ victims,
-                                                const Ctl* ctl) {
+__device__ __forceinline__ void insert_body(const CacheState& c, int policy, int32_t dim, const float* __restrict__ store,
+                                            const int32_t* __restrict__ new_ids, const int32_t* __restrict__ victims, const Ctl* ctl,
+                                            int64_t bid) {
     const int lane = threadIdx.x & (kWave - 1);
-    const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t i = bid * 4 + (threadIdx.x >> 6);
     if (i >= ctl->m) return;
     const int32_t s = victims[i], id = new_ids[i];
     if (lane == 0) {
@@ -417,6 +477,20 @@ __global__ void __launch_bounds__(256) k_insert(CacheState c, int policy, int32_
     const float* __restrict__ src = store + (int64_t)id * dim;
     float* __restrict__ dst = c.rows + (int64_t)s * dim;
     for (int32_t k = lane; k < dim; k += kWave) dst[k] = src[k];
+}
+
+// The insertion (workgroups [0, insert_blocks)) and the clearing of the batch's first-occurrence marks (the rest),
+// which touch different arrays, in one launch at the end of the fetch.
+__global__ void __launch_bounds__(256) k_insert_clear(CacheState c, int policy, int32_t dim, const float* __restrict__ store,
+                                                      const int32_t* __restrict__ new_ids, const int32_t* __restrict__ victims,
+                                                      const Ctl* ctl, int64_t insert_blocks, int64_t B,
+                                                      const int32_t* __restrict__ ids, const int32_t* __restrict__ slots) {
+    if ((int64_t)blockIdx.x < insert_blocks) {
+        insert_body(c, policy, dim, store, new_ids, victims, ctl, blockIdx.x);
+    } else {
+        const int64_t b = ((int64_t)blockIdx.x - insert_blocks) * 256 + threadIdx.x;
+        if (b < B && slots[b] == -1) c.first_idx[ids[b]] = kNoIndex;
+    }
 }
 
 inline unsigned blocks_for(int64_t n, int per = 256) { return (unsigned)std::max<int64_t>(1, (n + per - 1) / per); }
@@ -573,39 +647,64 @@ int tns_cache_fetch(tns_cache* cache, int64_t B, const int32_t* d_ids, const flo
         hipLaunchKernelGGL(k_gather<1>, dim3(blocks_for((B * dim + kGatherUnroll - 1) / kGatherUnroll)), dim3(256), 0, stream, st.rows, store, dim, B, N, d_ids,
                            st.slot_of, d_out);
 
-    hipLaunchKernelGGL(k_lookup, dim3(blocks_for((B + kLookupUnroll - 1) / kLookupUnroll)), dim3(256), 0, us, st, policy, N, B, d_ids, w.slots, d_hit, w.ctl);
+    hipLaunchKernelGGL(k_lookup, dim3(blocks_for((B + kLookupUnroll - 1) / kLookupUnroll)), dim3(256), 0, us, st, policy, N, B, d_ids,
+                       w.slots, d_hit, w.ctl);
     // LRU: every score is decremented and the accessed entries are reset; done on the way by the first
     // pass of the victim selection when there is one
     if (policy == TNS_CACHE_LRU && !select)
         hipLaunchKernelGGL(k_lru_scores, dim3(blocks_for(C)), dim3(256), 0, us, st.score, st.touched, C);
     if (maxrep > 0) {
-        compact_flagged(NewIds{st.first_idx, d_ids, w.slots, maxrep, w.new_ids, w.ctl}, B, w.sums, us);
+        const NewIds nf{st.first_idx, d_ids, w.slots, maxrep, w.new_ids, w.ctl};
+        // few workgroups for the histograms: they are added to one global one with atomics
+        const unsigned hb = (unsigned)std::min<int64_t>(blocks_for(C), 256);
+        const int64_t tiles_b = (B + kScanTile - 1) / kScanTile;
+        const bool lru = policy == TNS_CACHE_LRU;
+        if (select && tiles_b <= kFoldTiles) {
+            // distinct missed ids: tile sums, then the collect kernel, which shares its launch with pass 0 of the selection
+            hipLaunchKernelGGL((k_flag_tile_sums<NewIds>), dim3((unsigned)tiles_b), dim3(256), 0, us, nf, B, w.sums);
+            if (lru)
+                hipLaunchKernelGGL((k_newids_collect_hist0<true>), dim3((unsigned)tiles_b + hb), dim3(256), 0, us, nf, B, w.sums, tiles_b,
+                                   st.score, st.touched, C, w.ctl, (int64_t)hb);
+            else
+                hipLaunchKernelGGL((k_newids_collect_hist0<false>), dim3((unsigned)tiles_b + hb), dim3(256), 0, us, nf, B, w.sums, tiles_b,
+                                   st.score, st.touched, C, w.ctl, (int64_t)hb);
+        } else {
+            compact_flagged(nf, B, w.sums, us);
+            if (select) {
+                if (lru) hipLaunchKernelGGL(k_select_hist<true>, dim3(hb), dim3(256), 0, us, st.score, st.touched, C, 0, w.ctl);
+                else hipLaunchKernelGGL(k_select_hist<false>, dim3(hb), dim3(256), 0, us, st.score, st.touched, C, 0, w.ctl);
+            }
+        }
         if (policy == TNS_CACHE_FIFO) {
             hipLaunchKernelGGL(k_fifo_victims, dim3(blocks_for(maxrep)), dim3(256), 0, us, C, maxrep, st.ring, w.ctl, w.victims);
             hipLaunchKernelGGL(k_fifo_advance, dim3(1), dim3(1), 0, us, C, st.ring, w.ctl);
         } else {
-            // few workgroups: their histograms are added to one global one with atomics
-            const unsigned hb = (unsigned)std::min<int64_t>(blocks_for(C), 256);
-            for (int shift = 24; shift >= 0; shift -= 8) {
-                if (shift == 24 && policy == TNS_CACHE_LRU)
-                    hipLaunchKernelGGL(k_select_hist<true>, dim3(hb), dim3(256), 0, us, st.score, st.touched, C, shift, w.ctl);
-                else
-                    hipLaunchKernelGGL(k_select_hist<false>, dim3(hb), dim3(256), 0, us, st.score, st.touched, C, shift, w.ctl);
-                hipLaunchKernelGGL(k_select_digit, dim3(1), dim3(256), 0, us, shift, w.ctl);
+            // passes 1-3: each picks the digit of the pass before it in its prologue
+            for (int pass = 1; pass < 4; ++pass)
+                hipLaunchKernelGGL(k_select_hist<false>, dim3(hb), dim3(256), 0, us, st.score, st.touched, C, pass, w.ctl);
+            // victims in slot order; the tile-sum kernel picks the last digit first
+            const Victims vf{st.score, w.ctl, w.victims};
+            const int64_t tiles_c = (C + kScanTile - 1) / kScanTile;
+            hipLaunchKernelGGL(k_victims_tile_sums, dim3((unsigned)std::max<int64_t>(tiles_c, 1)), dim3(256), 0, us, vf, w.ctl, C, w.sums);
+            if (tiles_c <= kFoldTiles) {
+                hipLaunchKernelGGL((k_flag_collect<Victims, true>), dim3((unsigned)std::max<int64_t>(tiles_c, 1)), dim3(256), 0, us, vf, C, w.sums);
+            } else {
+                hipLaunchKernelGGL((k_flag_scan_sums<Victims>), dim3(1), dim3(1024), 0, us, vf, w.sums, tiles_c);
+                hipLaunchKernelGGL((k_flag_collect<Victims, false>), dim3((unsigned)tiles_c), dim3(256), 0, us, vf, C, w.sums);
             }
-            compact_flagged(Victims{st.score, w.ctl, w.victims}, C, w.sums, us);
         }
     }
-    // the first-occurrence marks of this batch are cleared for the next one (after the distinct misses were collected)
-    hipLaunchKernelGGL(k_clear_first, dim3(blocks_for(B)), dim3(256), 0, us, st.first_idx, B, d_ids, w.slots);
     {
         hipError_t ej = hipEventRecord(cache->joined, us);
         if (ej == hipSuccess) ej = hipStreamWaitEvent(stream, cache->joined, 0);
         if (ej != hipSuccess) return fail_hip(ej, "joining the cache update");
     }
-    if (maxrep > 0)
-        hipLaunchKernelGGL(k_insert, dim3(blocks_for(maxrep, 4)), dim3(256), 0, stream, st, policy, dim, store, w.new_ids, w.victims,
-                           w.ctl);
+    // the insertion, and the clearing of this batch's first-occurrence marks for the next one, in one launch
+    {
+        const int64_t ib = maxrep > 0 ? (int64_t)blocks_for(maxrep, 4) : 0;
+        hipLaunchKernelGGL(k_insert_clear, dim3((unsigned)(ib + blocks_for(B))), dim3(256), 0, stream, st, policy, dim, store, w.new_ids,
+                           w.victims, w.ctl, ib, B, d_ids, w.slots);
+    }
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail_hip(e, "launching the cache kernels");
     return TNS_OK;

@@ -47,6 +47,38 @@ def test_tiny_streams_all_options(B, oracle_lib, policy, inclusive, f):
 
 
 @pytest.mark.parametrize("policy", [0, 1])
+@pytest.mark.parametrize("f", [1, 3, 10, 16])
+def test_degrees_around_the_line_boundaries(B, oracle_lib, policy, f):
+    """Node v ends with degree v (0..71): every fill of the node's own line (8 slots), of each extension line of the
+    prefix layout (18, 28, 38) and of the first blocks outside it, with many equal timestamps across those
+    boundaries; ingested one edge, a few edges and all edges per batch (three different block structures); queried at
+    every event and a little before / after every distinct time, half-open and closed, with and without a window."""
+    rng = np.random.default_rng(77)
+    num_nodes = 72
+    src = np.repeat(np.arange(num_nodes, dtype=np.int32), np.arange(num_nodes))
+    rng.shuffle(src)
+    n = len(src)
+    dst = rng.integers(0, num_nodes, n, dtype=np.int32)
+    ts = np.sort(rng.integers(0, 300, n)).astype(np.float32)
+    times = np.unique(ts)
+    q_t = np.concatenate([times, np.nextafter(times, np.float32(-np.inf)), np.nextafter(times, np.float32(np.inf))]).astype(np.float32)
+    q_v = rng.integers(0, num_nodes, len(q_t), dtype=np.int32)
+    targets = np.concatenate([src, q_v, np.repeat(np.arange(num_nodes, dtype=np.int32), 4)])
+    t_end = np.concatenate([ts, q_t, np.tile(np.array([-1.0, 150.0, 299.0, 1e9], np.float32), num_nodes)])
+    t_start = (t_end - np.float32(40.0)).astype(np.float32)
+    for batch in (1, 37, n):
+        st = W.Stream(num_nodes, src, dst, ts, batch)
+        wl = wl_of(st, fanout=f)
+        for incl in (0, 1):
+            plan = build_plan(B, wl, policy, incl, seed=9)
+            for tb in (None, t_start):
+                got = gpu_sample(plan, targets, tb, t_end)
+                ref = oracle_sample(oracle_lib, wl, targets, tb, t_end, None, f, policy, incl, 9)
+                assert_same(got, ref, oracle_lib, f"batch={batch} incl={incl} window={'y' if tb is not None else 'n'}")
+            plan.close()
+
+
+@pytest.mark.parametrize("policy", [0, 1])
 @pytest.mark.parametrize("f", [3, 10, 20])
 def test_64_bit_edge_positions(B, oracle_lib, policy, f):
     # the kernels keep 64-bit positions once the edge array passes 8 GiB; forced here on a small store

@@ -99,7 +99,7 @@ def main() -> int:
         "store": stats,
         "roofline": {"bound": "hbm", "achieved": alg / sec / 1e9, "peak": 8000.0, "unit": "GB/s",
                      "frac": alg / sec / 1e9 / 8000.0, "traffic": None, "algorithmic_bytes": alg,
-                     "note": "batches of at most 2^18 edges: 7 launches and one status read-back per batch; larger ones about 45 launches; bound by launches and dependent reads, not by bandwidth"},
+                     "note": "batches of at most 2^21 edges: 7 launches and one status hand-over per batch; larger ones about 45 launches; bound by launches and dependent reads, not by bandwidth"},
         "host_builder": {"value": k_host / host_s, "unit": "edges/s", "cores": 1,
                          "sample": f"tns_add_edges on the first {k_host} edges, {host_s:.1f} s"},
         "cpu_baseline": cpu,

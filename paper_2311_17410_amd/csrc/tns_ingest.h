@@ -75,7 +75,7 @@ size_t ingest_workspace_bytes(int64_t m);
 // against what is stored, and compute what every node needs (edge lines, directory records).
 // Changes nothing in the store.  The host then reads *status, makes room, and runs phase 2.
 hipError_t ingest_plan(const IngestArgs& a, hipStream_t stream);
-// The same phase in five launches for batches of stream size (at most 2^18 edges, at most 2^24 nodes) that
+// The same phase in five launches for batches of stream size (at most 2^21 edges, at most 2^24 nodes) that
 // arrive in time order: it sorts by source only and reports status->unsorted when the batch was not in time
 // order, in which case the caller runs ingest_plan instead.  Expects *status reset (ingest_apply leaves it so).
 bool ingest_fast_ok(int64_t m, int64_t num_nodes);

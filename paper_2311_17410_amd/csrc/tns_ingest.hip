@@ -535,8 +535,8 @@ constexpr int kFastItems = 16;                          // keys per thread and t
 constexpr int kFastTile = kThreads * kFastItems;        // 4096 keys per tile
 constexpr int kScatThreads = 512;                       // the radix passes: 8 waves x 8 keys per lane on the same tiles
 constexpr int kScatItems = kFastTile / kScatThreads;
-constexpr int kFastMaxTiles = 64;
-constexpr int64_t kFastMaxBatch = (int64_t)kFastTile * kFastMaxTiles;   // 2^18 edges
+constexpr int kFastMaxTiles = 512;
+constexpr int64_t kFastMaxBatch = (int64_t)kFastTile * kFastMaxTiles;   // 2^21 edges
 constexpr int kFastMaxBits = 12;                        // bits per digit: two digits cover 2^24 nodes
 constexpr int kSegItems = 4;                            // positions per thread in k_fast_segments
 constexpr int kPlanThreads = 1024;                      // k_fast_plan: one segment per thread, 1024 per tile

@@ -186,3 +186,31 @@ def test_instances_and_c2_c3(B, oracle_lib):
         plan.close()
         for a in adjs:
             a.close()
+
+
+@pytest.mark.parametrize("batch", [1_500_000, 2_500_000])
+def test_large_batches_through_both_pipelines(B, oracle_lib, batch):
+    """Zipf stream of 2^22 edges in ragged batches of 1.5 M edges (the short planning pipeline: at most 2^21 edges per
+    batch, here 367 sort tiles with a ragged last one) and of 2.5 M edges (the general pipeline): sampling equals the
+    definition, block statistics equal the host builder's on the same batches."""
+    wl = W.c3(log2_n=22)
+    st = wl.streams[0]
+    progress(f"device ingestion of 2^22 edges in batches of {batch}")
+    plan = device_plan(B, wl, 0, seed=wl.seed, batch=batch)
+    targets, t_start, t_end, _ = wl.queries(window_frac=0.25)
+    adj = oracle_lib.Adjacency(st.num_nodes, st.src, st.dst, st.ts)
+    for policy in (0, 1):
+        plan.set_sampler(wl.fanout, policy, 0, wl.seed)
+        got = gpu_sample(plan, targets, t_start, t_end)
+        ref = oracle_sample(oracle_lib, wl, targets, t_start, t_end, None, wl.fanout, policy, 0, wl.seed, threads=16, adjs=[adj])
+        assert_same(got, ref, oracle_lib, f"batch={batch} policy={policy}")
+    host = B.Plan(wl.num_nodes, wl.fanout, block_threshold=wl.tau)
+    for lo in range(0, st.n, batch):
+        hi = min(lo + batch, st.n)
+        B.tns_add_edges(host.handle, 0, st.src[lo:hi], st.dst[lo:hi], st.ts[lo:hi], None)
+    hs, ds = host.stats(), plan.stats()
+    for k in ("num_blocks", "num_edges", "wasted_slots", "max_list_len"):
+        assert hs[k] == ds[k], k
+    host.close()
+    plan.close()
+    adj.close()

@@ -33,6 +33,8 @@ def main() -> int:
     ap.add_argument("--batch", type=int, default=0,
                     help="first-hop queries: the last BATCH events of the stream (a training mini-batch, section 6: 600-4000 "
                          "edges) instead of every event")
+    ap.add_argument("--layout", default="blocks", choices=["blocks", "prefix"],
+                    help="blocks: store built on the device in the default layout; prefix: host-built store in the prefix layout")
     ap.add_argument("--graph", action="store_true", help="capture the call into a HIP graph once and time replays")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -49,11 +51,18 @@ def main() -> int:
     wl = W.c5(log2_n=args.log2n)
     st = wl.streams[0]
     Q = st.n
-    plan = B.Plan(st.num_nodes, fanouts[0], block_threshold=wl.tau, flags=B.TNS_FLAG_DEVICE_INGEST)
     d_src, d_dst, d_ts = (torch.from_numpy(a).to(dev) for a in (st.src, st.dst, st.ts))
-    for lo, hi in st.batches():
-        plan.add_edges_device(d_src[lo:hi], d_dst[lo:hi], d_ts[lo:hi])
+    if args.layout == "prefix":
+        plan = B.Plan(st.num_nodes, fanouts[0], block_threshold=wl.tau, flags=B.TNS_FLAG_PREFIX_LAYOUT)
+        for lo, hi in st.batches():
+            B.tns_add_edges(plan.handle, 0, st.src[lo:hi], st.dst[lo:hi], st.ts[lo:hi], None)
+        plan.commit()
+    else:
+        plan = B.Plan(st.num_nodes, fanouts[0], block_threshold=wl.tau, flags=B.TNS_FLAG_DEVICE_INGEST)
+        for lo, hi in st.batches():
+            plan.add_edges_device(d_src[lo:hi], d_dst[lo:hi], d_ts[lo:hi])
     del d_dst
+    node_entry = 32 if args.layout == "prefix" else 16
 
     q_src, q_ts, h_src, h_ts = d_src, d_ts, st.src, st.ts
     if args.batch:
@@ -99,7 +108,7 @@ def main() -> int:
         B.tns_traffic_model(plan.handle, q, p(targets), 0, p(t_end), 0, 0, counters.data_ptr(), stream)
         torch.cuda.synchronize()
         nn, nb, npr, ne = (int(x) for x in counters.cpu())
-        alg += 8 * q + 16 * nn + 16 * nb + 4 * npr + 12 * ne + (12 * f + 4) * q + 8 * (q + 1) + 12 * ne
+        alg += 8 * q + node_entry * nn + 16 * nb + 4 * npr + 12 * ne + (12 * f + 4) * q + 8 * (q + 1) + 12 * ne
         targets, t_end = h["cmp_nbr"], h["cmp_ts"]
     total_q = sum(n_q)
 
@@ -126,7 +135,7 @@ def main() -> int:
         "config": {"workload": f"{wl.name} recipe, n=2^{args.log2n}: "
                                + (f"first-hop queries = the last {Q} events" if args.batch else "one first-hop query per event")
                                + f", fan-outs {fanouts}, recent policy, unbounded window, hop h+1 = dense output of hop h",
-                   "queries_per_hop": n_q, "hip_graph_replay": bool(args.graph)},
+                   "queries_per_hop": n_q, "hip_graph_replay": bool(args.graph), "layout": args.layout},
         "roofline": {"bound": "hbm", "achieved": alg / (ms_gpu * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
                      "frac": alg / (ms_gpu * 1e-3) / 1e9 / 8000.0, "traffic": None, "algorithmic_bytes_per_step": alg,
                      "ms_gpu_per_step": ms_gpu},

@@ -35,6 +35,7 @@ def main() -> int:
                          "edges) instead of every event")
     ap.add_argument("--layout", default="blocks", choices=["blocks", "prefix"],
                     help="blocks: store built on the device in the default layout; prefix: host-built store in the prefix layout")
+    ap.add_argument("--dense-only", action="store_true", help="pass no padded outputs: every hop writes its dense result only")
     ap.add_argument("--graph", action="store_true", help="capture the call into a HIP graph once and time replays")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -72,6 +73,9 @@ def main() -> int:
     torch.cuda.synchronize()
     p = lambda t: 0 if t is None else t.data_ptr()
     ptrs = [{k: p(v) for k, v in h.items() if k not in ("cap", "fanout")} for h in hops]
+    if args.dense_only:
+        for d in ptrs:
+            d["nbr"] = d["eid"] = d["ts"] = d["count"] = 0
     stream = torch.cuda.current_stream().cuda_stream
 
     def step():
@@ -108,7 +112,7 @@ def main() -> int:
         B.tns_traffic_model(plan.handle, q, p(targets), 0, p(t_end), 0, 0, counters.data_ptr(), stream)
         torch.cuda.synchronize()
         nn, nb, npr, ne = (int(x) for x in counters.cpu())
-        alg += 8 * q + node_entry * nn + 16 * nb + 4 * npr + 12 * ne + (12 * f + 4) * q + 8 * (q + 1) + 12 * ne
+        alg += 8 * q + node_entry * nn + 16 * nb + 4 * npr + 12 * ne + (0 if args.dense_only else (12 * f + 4) * q) + 8 * (q + 1) + 12 * ne
         targets, t_end = h["cmp_nbr"], h["cmp_ts"]
     total_q = sum(n_q)
 
@@ -135,7 +139,7 @@ def main() -> int:
         "config": {"workload": f"{wl.name} recipe, n=2^{args.log2n}: "
                                + (f"first-hop queries = the last {Q} events" if args.batch else "one first-hop query per event")
                                + f", fan-outs {fanouts}, recent policy, unbounded window, hop h+1 = dense output of hop h",
-                   "queries_per_hop": n_q, "hip_graph_replay": bool(args.graph), "layout": args.layout},
+                   "queries_per_hop": n_q, "hip_graph_replay": bool(args.graph), "layout": args.layout, "dense_only": bool(args.dense_only)},
         "roofline": {"bound": "hbm", "achieved": alg / (ms_gpu * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
                      "frac": alg / (ms_gpu * 1e-3) / 1e9 / 8000.0, "traffic": None, "algorithmic_bytes_per_step": alg,
                      "ms_gpu_per_step": ms_gpu},

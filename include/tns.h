@@ -264,7 +264,9 @@ TNS_API int tns_run_static(tns_plan *plan, int64_t Q, const int32_t *d_targets, 
  * (delta = +infinity: unbounded).  A temporal random walk is the special case fanouts = 1,1,...
  *
  *   fanouts[num_hops]   HOST; each in 1..TNS_MAX_FANOUT (the plan's own fan-out is not used)
- *   hops[num_hops]      HOST array of DEVICE buffer sets, all fields required.  With
+ *   hops[num_hops]      HOST array of DEVICE buffer sets; rowptr and the three dense arrays are required,
+ *                       the four padded outputs of a hop (nbr, eid, ts, count) may be NULL together: the hop
+ *                       then writes its dense result only, which is all the next hop reads.  With
  *                       cap_1 = Q and cap_{h+1} = cap_h * fanouts[h] (the most queries hop h can
  *                       have), hop h needs nbr/eid/ts[cap_h * fanouts[h]], count[cap_h],
  *                       rowptr[cap_h + 1], cmp_nbr/eid/ts[cap_h * fanouts[h]].  Only the entries

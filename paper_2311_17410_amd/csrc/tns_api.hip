@@ -803,7 +803,9 @@ int tns_run_khop(tns_plan* plan, int32_t num_hops, const int32_t* fanouts, float
     if (reinterpret_cast<uintptr_t>(d_workspace) & 255) return fail(TNS_EINVAL, "workspace must be 256-byte aligned");
     for (int h = 0; h < num_hops; ++h) {
         const tns_hop_buffers& b = hops[h];
-        if (!b.rowptr || (caps[h] > 0 && (!b.nbr || !b.eid || !b.ts || !b.count || !b.cmp_nbr || !b.cmp_eid || !b.cmp_ts)))
+        // the four padded outputs of a hop may be null together: only its dense result is written then
+        const bool no_padded = !b.nbr && !b.eid && !b.ts && !b.count;
+        if (!b.rowptr || (caps[h] > 0 && (!b.cmp_nbr || !b.cmp_eid || !b.cmp_ts || (!no_padded && (!b.nbr || !b.eid || !b.ts || !b.count)))))
             return fail(TNS_EINVAL, "null buffer in hops[]");
     }
     tns::SampleArgs a;

@@ -350,6 +350,47 @@ def test_khop_matches_chained_oracle(B, oracle_lib, policy, fanouts, delta):
     plan.close()
 
 
+@pytest.mark.parametrize("policy", [0, 1])
+def test_khop_without_padded_outputs(B, oracle_lib, policy):
+    """Hops whose four padded outputs are NULL write their dense result only: rowptr and the dense arrays of every hop
+    equal the oracle chain's; a hop that passes some padded outputs but not all is refused."""
+    import torch
+    fanouts, delta = [10, 3, 12], 25.0
+    st = W.tiny_stream(93, 4000, 37, 256, ties=True)
+    wl = wl_of(st, fanout=fanouts[0])
+    plan = build_plan(B, wl, policy, 0, seed=9)
+    targets, t_start, t_end = W.random_queries(94, st, 700 + 5)
+    dev = torch.device("cuda", 0)
+    d = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    d_t, d_b, d_e = d(targets), d(t_start), d(t_end)
+    hops, ws = plan.run_khop(fanouts, d_t, d_b, d_e, delta=delta)          # allocates the buffers; result overwritten below
+    torch.cuda.synchronize()
+    for h in hops:
+        for k in ("rowptr", "cmp_nbr", "cmp_eid", "cmp_ts"):
+            h[k].fill_(-7)
+    p = lambda t: t.data_ptr()
+    ptrs = [dict(nbr=0, eid=0, ts=0, count=0, rowptr=p(h["rowptr"]), cmp_nbr=p(h["cmp_nbr"]), cmp_eid=p(h["cmp_eid"]), cmp_ts=p(h["cmp_ts"]))
+            for h in hops]
+    B.tns_run_khop(plan.handle, fanouts, delta, len(targets), p(d_t), p(d_b), p(d_e), 0, 0, ptrs, ws.data_ptr(), ws.numel(),
+                   torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert not plan.status(ws)
+    ref = oracle_khop(oracle_lib, wl, targets, t_start, t_end, None, fanouts, delta, policy, 9, base=0)
+    n = len(targets)
+    for h, (r, rowptr, cn, ce, ct) in enumerate(ref):
+        g = hops[h]
+        assert np.array_equal(g["rowptr"][:n + 1].cpu().numpy(), rowptr), f"hop {h} rowptr"
+        tot = int(rowptr[-1])
+        assert np.array_equal(g["cmp_eid"][:tot].cpu().numpy(), ce) and np.array_equal(g["cmp_nbr"][:tot].cpu().numpy(), cn)
+        assert np.array_equal(g["cmp_ts"][:tot].cpu().numpy().view(np.int32), ct.view(np.int32))
+        n = tot
+    ptrs[1]["count"] = p(hops[1]["count"])            # some padded outputs but not all
+    with pytest.raises(B.TnsError):
+        B.tns_run_khop(plan.handle, fanouts, delta, len(targets), p(d_t), p(d_b), p(d_e), 0, 0, ptrs, ws.data_ptr(), ws.numel(),
+                       torch.cuda.current_stream().cuda_stream)
+    plan.close()
+
+
 def test_khop_batched_instances_and_c2(B, oracle_lib):
     import torch
     dev = torch.device("cuda", 0)

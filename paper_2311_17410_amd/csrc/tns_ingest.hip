@@ -531,12 +531,14 @@ __global__ void __launch_bounds__(kThreads) k_apply_edges(const IngestArgs a, co
 //   k_fast_plan      the per-segment plan and the pool offsets (two chained scans) in one launch.
 // Time order is assumed, not known: k_fast_keys sets `unsorted` as the general pipeline does, and
 // the host, which reads the status before anything is changed, then runs the general pipeline instead.
-constexpr int kFastItems = 16;                          // keys per thread and tile
-constexpr int kFastTile = kThreads * kFastItems;        // 4096 keys per tile
+// keys per sort tile: small batches take smaller tiles so that they still spread over the compute units, large ones
+// larger tiles so that the table of tile histograms every tile reads stays short (measured: 2^14 edges 0.071 / 0.090 ms
+// with 1024 / 4096 keys per tile, 2^17 edges 0.117 / 0.125 ms with 2048 / 4096, 2^20 edges 0.635 / 0.538 ms)
+constexpr int kFastTileMax = 4096;
+inline int fast_tile_keys(int64_t m) { return m <= (int64_t(1) << 16) ? 1024 : (m <= (int64_t(1) << 17) ? 2048 : kFastTileMax); }
 constexpr int kScatThreads = 512;                       // the radix passes: 8 waves x 8 keys per lane on the same tiles
-constexpr int kScatItems = kFastTile / kScatThreads;
 constexpr int kFastMaxTiles = 512;
-constexpr int64_t kFastMaxBatch = (int64_t)kFastTile * kFastMaxTiles;   // 2^21 edges
+constexpr int64_t kFastMaxBatch = (int64_t)kFastTileMax * kFastMaxTiles;   // 2^21 edges
 constexpr int kFastMaxBits = 12;                        // bits per digit: two digits cover 2^24 nodes
 constexpr int kSegItems = 4;                            // positions per thread in k_fast_segments
 constexpr int kPlanThreads = 1024;                      // k_fast_plan: one segment per thread, 1024 per tile
@@ -581,6 +583,7 @@ __device__ __forceinline__ int64_t chain_wave(ScanWorkspace* ws, IngestStatus* s
     return excl;
 }
 
+template <int TILE>
 __global__ void __launch_bounds__(kThreads) k_fast_keys(const IngestArgs a, uint64_t* __restrict__ key, uint32_t* __restrict__ val,
                                                         uint32_t* __restrict__ hist1, uint32_t* __restrict__ hist2, int bits,
                                                         ScanWorkspace* seg_scan, ScanWorkspace* lines_scan, ScanWorkspace* dir_scan,
@@ -589,7 +592,8 @@ __global__ void __launch_bounds__(kThreads) k_fast_keys(const IngestArgs a, uint
     const int bins = 1 << bits;
     for (int b = threadIdx.x; b < bins; b += kThreads) s_hist[b] = 0;
     __syncthreads();
-    const int64_t base = (int64_t)blockIdx.x * kFastTile;
+    constexpr int kFastItems = TILE / kThreads;
+    const int64_t base = (int64_t)blockIdx.x * TILE;
     int32_t v_[kFastItems], e_[kFastItems];
     float t_[kFastItems], tp_[kFastItems];
 #pragma unroll
@@ -638,10 +642,11 @@ __global__ void __launch_bounds__(kThreads) k_fast_keys(const IngestArgs a, uint
     }
 }
 
-// One stable radix pass over `bits` bits of the key starting at `shift`.  A wave owns kScatItems * 64
+// One stable radix pass over `bits` bits of the key starting at `shift`.  A wave owns TILE / 8
 // consecutive keys of the tile and takes them 64 at a time in order, so "earlier in the tile" is
 // (wave, item, lane) order; a key's rank among equal digits is the count of its wave so far plus its rank
 // among the lanes of the current item (ballots over the digit's bits).
+template <int TILE>
 __global__ void __launch_bounds__(kScatThreads) k_fast_scatter(const uint64_t* __restrict__ kin, const uint32_t* __restrict__ vin,
                                                            uint64_t* __restrict__ kout, uint32_t* __restrict__ vout, int64_t m,
                                                            int shift, int bits, int tiles, const uint32_t* __restrict__ hist,
@@ -716,7 +721,8 @@ __global__ void __launch_bounds__(kScatThreads) k_fast_scatter(const uint64_t* _
     for (int i = t; i < bins * (kScatThreads / kWave); i += kScatThreads) s_cnt[i] = 0;
     __syncthreads();
 
-    const int64_t wbase = (int64_t)tile * kFastTile + (int64_t)wave * (kScatItems * kWave);
+    constexpr int kScatItems = TILE / kScatThreads;
+    const int64_t wbase = (int64_t)tile * TILE + (int64_t)wave * (kScatItems * kWave);
     uint64_t k_[kScatItems];
     uint32_t v_[kScatItems], r_[kScatItems];
     uint32_t* my_cnt = s_cnt + (size_t)wave * bins;
@@ -767,7 +773,7 @@ __global__ void __launch_bounds__(kScatThreads) k_fast_scatter(const uint64_t* _
         if ((int64_t)pos < m) {                 // always true for consistent histograms; keeps a bad one in bounds
             kout[pos] = k_[j];
             vout[pos] = v_[j];
-            if (hist_next) atomicAdd(&hist_next[(size_t)(pos / kFastTile) * bins + ((uint32_t)(k_[j] >> shift_next) & mask)], 1u);
+            if (hist_next) atomicAdd(&hist_next[(size_t)(pos / TILE) * bins + ((uint32_t)(k_[j] >> shift_next) & mask)], 1u);
         }
     }
 }
@@ -963,7 +969,7 @@ Carve carve(void* ws, int64_t m) {
     c.seg_start = reinterpret_cast<int32_t*>(take((mm + 1) * 4));
     c.plan = reinterpret_cast<SegPlan*>(take(mm * sizeof(SegPlan)));
     if (m <= kFastMaxBatch) {
-        c.fast_tiles = (int)((mm + kFastTile - 1) / kFastTile);
+        c.fast_tiles = (int)((mm + fast_tile_keys(m) - 1) / fast_tile_keys(m));
         c.seg_tiles = (int)((mm + kThreads * kSegItems - 1) / (kThreads * kSegItems));
         c.plan_tiles = (int)((mm + kPlanThreads - 1) / kPlanThreads);
         for (int p2 = 0; p2 < 2; ++p2)
@@ -1042,13 +1048,23 @@ hipError_t ingest_plan_fast(const IngestArgs& a, hipStream_t stream) {
     if (a.m <= 0 || bits <= 0) return hipErrorInvalidValue;
     const Carve c = carve(a.workspace, a.m);
     const int bins = 1 << bits;
-    hipLaunchKernelGGL(k_fast_keys, dim3((unsigned)c.fast_tiles), dim3(kThreads), (size_t)bins * 4, stream, a, c.keyA, c.valA,
-                       c.tile_hist[0], c.tile_hist[1], bits, c.seg_scan, c.lines_scan, c.dir_scan, c.seg_tiles, c.plan_tiles);
     const size_t lds = (size_t)bins * 4 * (1 + kScatThreads / kWave);
-    hipLaunchKernelGGL(k_fast_scatter, dim3((unsigned)c.fast_tiles), dim3(kScatThreads), lds, stream, c.keyA, c.valA, c.keyB, c.valB, a.m,
-                       32, bits, c.fast_tiles, c.tile_hist[0], c.tile_hist[1], 32 + bits);
-    hipLaunchKernelGGL(k_fast_scatter, dim3((unsigned)c.fast_tiles), dim3(kScatThreads), lds, stream, c.keyB, c.valB, c.keyA, c.valA, a.m,
-                       32 + bits, bits, c.fast_tiles, c.tile_hist[1], (uint32_t*)nullptr, 0);
+#define TNS_FAST_SORT(TILE)                                                                                                          \
+    do {                                                                                                                             \
+        hipLaunchKernelGGL((k_fast_keys<TILE>), dim3((unsigned)c.fast_tiles), dim3(kThreads), (size_t)bins * 4, stream, a, c.keyA,  \
+                           c.valA, c.tile_hist[0], c.tile_hist[1], bits, c.seg_scan, c.lines_scan, c.dir_scan, c.seg_tiles,          \
+                           c.plan_tiles);                                                                                            \
+        hipLaunchKernelGGL((k_fast_scatter<TILE>), dim3((unsigned)c.fast_tiles), dim3(kScatThreads), lds, stream, c.keyA, c.valA,    \
+                           c.keyB, c.valB, a.m, 32, bits, c.fast_tiles, c.tile_hist[0], c.tile_hist[1], 32 + bits);                  \
+        hipLaunchKernelGGL((k_fast_scatter<TILE>), dim3((unsigned)c.fast_tiles), dim3(kScatThreads), lds, stream, c.keyB, c.valB,    \
+                           c.keyA, c.valA, a.m, 32 + bits, bits, c.fast_tiles, c.tile_hist[1], (uint32_t*)nullptr, 0);               \
+    } while (0)
+    switch (fast_tile_keys(a.m)) {
+        case 1024: TNS_FAST_SORT(1024); break;
+        case 2048: TNS_FAST_SORT(2048); break;
+        default: TNS_FAST_SORT(kFastTileMax); break;
+    }
+#undef TNS_FAST_SORT
     hipLaunchKernelGGL(k_fast_segments, dim3((unsigned)c.seg_tiles), dim3(kThreads), 0, stream, c.keyA, a.m, c.head_excl, c.seg_start,
                        c.seg_scan, a.status);
     hipLaunchKernelGGL(k_fast_plan, dim3((unsigned)c.plan_tiles), dim3(kPlanThreads), 0, stream, a, c.keyA, c.valA, c.seg_start, c.plan,

@@ -317,14 +317,23 @@ __device__ __forceinline__ void plan_segment(const IngestArgs& a, const uint64_t
     const uint32_t v = (uint32_t)(key[p0] >> 32);
     if ((uint64_t)v >= (uint64_t)a.num_nodes) return;      // out-of-range ids were reported with the keys
     const int64_t nidx = a.node_base + v;
+    // the node entry's header and its newest inline record lie side by side: both are requested at once, with the
+    // builder state and the segment's first timestamp, so that the plan is two dependent round trips, not four
     const uint4 h = *reinterpret_cast<const uint4*>(&a.nodes[nidx]);
+    const uint4 r0 = *(reinterpret_cast<const uint4*>(&a.nodes[nidx]) + 1);
+    const NodeAux ax = a.aux[nidx];
+    const float t_first = a.ts[val[p0]];
     NodeLine nd;
     nd.nblocks = (int32_t)h.x; nd.degree = (int32_t)h.y; nd.dir_line = h.z;
-    const NodeAux ax = a.aux[nidx];
     int64_t room = 0;
     if (nd.nblocks > 0) {
-        const BlockRec tr = *tail_of(a, nd, nidx);
-        if (a.ts[val[p0]] < tr.t_max) report(a.status, TNS_EORDER, a.m + (int64_t)v);
+        BlockRec tr;
+        if (nd.nblocks <= kInlineBlocks) {
+            tr.t_min = __uint_as_float(r0.x); tr.t_max = __uint_as_float(r0.y); tr.off_lo = r0.z; tr.size_hi = r0.w;
+        } else {
+            tr = *tail_of(a, nd, nidx);
+        }
+        if (t_first < tr.t_max) report(a.status, TNS_EORDER, a.m + (int64_t)v);
         room = ax.tail_cap - rec_size(tr);
         P.tail_slot = rec_off(tr) + rec_size(tr);
     }
